@@ -1,0 +1,187 @@
+/*
+ * decdec.h - C ABI of the DecDEC decode-step hot path for AMD MI355X (gfx950).
+ *
+ * One call computes, for one linear layer at batch 1,
+ *
+ *     o = W_hat x  +  R_hat[sc_indices, :]^T x[sc_indices]
+ *
+ * where W_hat is the de-quantised 3/4-bit weight matrix resident in GPU
+ * memory, R_hat the residual W - W_hat resident in pinned CPU memory, and
+ * sc_indices the k input channels with the largest |x| of THIS step
+ * (DecDEC, Section 3.1 "(W_hat + R o M) x" and Section 4.1 steps 1-4).
+ *
+ * Orientation (Section 3.1-3.2, 4.2): a weight matrix is d_in x d_out = K x N;
+ * an input channel is a row, an output channel a column.  x has K entries,
+ * o has N entries.
+ *
+ * Conventions
+ *   - "dev"  pointer: GPU memory (hipMalloc / a torch CUDA tensor).
+ *   - "host" pointer: ordinary CPU memory, touched only by the host helpers.
+ *   - "pinned" pointer: page-locked, GPU-mapped CPU memory (hipHostMalloc or
+ *     a torch tensor with pin_memory=True); kernels read it in place over the
+ *     host link (Section 4.3 "Zero-Copy Residual Fetch").
+ *   - fp16 = IEEE binary16.  All multi-dimensional arrays are row-major.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Hot-path calls only enqueue work: no allocation, no host
+ *     synchronisation.  When a call returns, `stream` is ordered after the
+ *     result.  Pointers are borrowed until that work has run.
+ *   - Every function returns a decdec_status (0 = OK, negative = error);
+ *     nothing throws, aborts or prints.  On error nothing has been enqueued.
+ *   - A workspace serialises its users: calls that share one decdec_ws must
+ *     be issued on one stream (or otherwise ordered); use one workspace per
+ *     concurrent stream.
+ */
+#ifndef DECDEC_H
+#define DECDEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DECDEC_OK = 0,
+    DECDEC_EINVAL = -1,       /* null pointer, size or k out of range, bad alignment */
+    DECDEC_EUNSUPPORTED = -2, /* format / bit-width combination not implemented */
+    DECDEC_ENOTPINNED = -3,   /* residual pointer is not GPU-visible host memory */
+    DECDEC_EHIP = -4,         /* a HIP runtime call failed; see decdec_last_hip_error */
+    DECDEC_ENOMEM = -5        /* workspace allocation failed */
+} decdec_status;
+
+/* Base-weight formats (what the base GEMV de-quantises).
+ *   UNIFORM_G128: b-bit codes, b in {3,4}; W_hat[k][n] = s[k/128][n] * (q[k][n] - z[k/128][n])
+ *                 with fp16 scale s and integer-valued fp16 zero point z per
+ *                 output column per 128 consecutive input channels
+ *                 (Section 2.2: weights are de-quantised on the fly to fp16
+ *                 and multiplied with fp16 activations).
+ *   LUT_COL8:     3-bit codes into one ascending 8-entry fp16 codebook per
+ *                 output column: W_hat[k][n] = lut[n][c[k][n]] (the
+ *                 clustering-based non-uniform quantisation of Section 5.2).
+ */
+typedef enum { DECDEC_W_UNIFORM_G128 = 0, DECDEC_W_LUT_COL8 = 1 } decdec_wfmt;
+
+/* Residual formats in pinned CPU memory (Section 4.2).
+ *   FP16:          R[K][N] fp16, each input-channel row contiguous.
+ *   INT4_SYM_COL:  4-bit symmetric codes in [-7, 7], one fp16 scale per
+ *                  output column: R_hat[k][n] = S[n] * q[k][n].  Row k is
+ *                  N/2 contiguous bytes; byte j holds column 2j in its low
+ *                  nibble and column 2j+1 in its high nibble, each a 4-bit
+ *                  two's-complement integer.
+ */
+typedef enum { DECDEC_R_FP16 = 0, DECDEC_R_INT4_SYM_COL = 1 } decdec_rfmt;
+
+typedef struct {
+    int32_t K;      /* input channels  (d_in),  multiple of 128 */
+    int32_t N;      /* output channels (d_out), multiple of 64  */
+    int32_t wbits;  /* 3 or 4 (LUT_COL8: 3) */
+    int32_t wfmt;   /* decdec_wfmt */
+    int32_t rfmt;   /* decdec_rfmt */
+} decdec_desc;
+
+typedef struct decdec_ws decdec_ws; /* opaque workspace */
+
+/* ------------------------------------------------------------------ set-up */
+
+/* Allocates everything the hot path needs for problems up to (maxK, maxN)
+ * with up to maxk salient channels: a side stream and two events for the
+ * overlap of Section 4.1, the sc_indices / x[sc_indices] buffer of
+ * maxk*(4+2) bytes (Section 4.3 "GPU Memory Overhead"), and fp32 partial
+ * output buffers.  One workspace can be reused for every layer. */
+int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out);
+int decdec_ws_destroy(decdec_ws* ws);
+/* Size in bytes of the sc_indices + x[sc_indices] buffer for k channels. */
+size_t decdec_sc_buffer_bytes(int32_t k);
+/* Device pointers to the selection of the most recent decdec_gemv call on
+ * this workspace (valid once that call's work has run). */
+int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const void** xsel_f16_dev);
+/* Diagnostic, synchronous: waits for the workspace's side stream and copies
+ * the first k entries of that selection to host arrays (either may be NULL). */
+int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, void* xsel_f16_host);
+
+/* Number of fetch workgroups per output-column block the residual kernel
+ * uses (the counterpart of n_tb in Section 4.4); 0 restores the built-in
+ * choice.  Affects later calls on this workspace. */
+int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
+
+/* ------------------------------------------------- host helpers (offline) */
+
+/* Bytes of the library-private packed form of the K x N code matrix. */
+size_t decdec_packed_bytes(const decdec_desc* d);
+/* codes_KN: host uint8 [K][N], one code per byte (values < 2^wbits).
+ * out_packed: host buffer of decdec_packed_bytes(d); copy it to the GPU and
+ * pass it as Wq.  The packed layout is private to the library. */
+int decdec_pack_weights(const decdec_desc* d, const uint8_t* codes_KN, void* out_packed);
+/* Inverse of decdec_pack_weights (host), for checking. */
+int decdec_unpack_weights(const decdec_desc* d, const void* packed, uint8_t* codes_KN);
+/* codes: host int8 [K][N] in [-7,7] -> out: host bytes [K][N/2] in the
+ * INT4_SYM_COL row format above. */
+int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint8_t* out);
+
+/* ------------------------------------------------------------ hot path */
+
+/* Step 1 of Section 4.1 with the exact Top-K of Section 5.2: writes the k
+ * indices i with the largest |x_i| in ascending index order (a tie at the cut
+ * goes to the lower index; |x| is ordered by the fp16 bit pattern with the
+ * sign cleared, so -0 == +0 and NaN patterns rank above infinity) and, if
+ * xsel_f16_dev is not NULL, x at those indices.
+ *   x_f16_dev: dev fp16 [K], 16-byte aligned, K a multiple of 8, 8 <= K <= 65536;
+ *   0 <= k <= K.
+ *   idx_out_dev: dev int32 [k];  xsel_f16_dev: dev fp16 [k] or NULL.
+ * k == 0 enqueues nothing. */
+int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k,
+                       int32_t* idx_out_dev, void* xsel_f16_dev, void* stream);
+
+/* The whole path (Section 4.1 steps 1-4 beside the base GEMV):
+ *   y = W_hat x + R_hat[sc,:]^T x[sc],  sc = top-k of |x|.
+ *   x_f16_dev      dev fp16 [K]
+ *   Wq_dev         dev, packed by decdec_pack_weights (or decdec_quantize_uniform)
+ *   scales_f16_dev dev fp16 [K/128][N]           (UNIFORM; ignored for LUT)
+ *   zeros_or_lut   dev fp16 [K/128][N] zero points (UNIFORM) or fp16 [N][8] (LUT)
+ *   R_pinned       pinned fp16 [K][N] or int4 bytes [K][N/2]; may be NULL if k == 0
+ *   R_scales_f16_dev dev fp16 [N] (INT4_SYM_COL only, else NULL)
+ *   k              salient channels, 0 <= k <= min(K, maxk of ws)
+ *   y_f16_dev      dev fp16 [N] out
+ * The base GEMV runs on `stream`; selection, zero-copy fetch and residual
+ * GEMV run on the workspace's side stream, concurrently; the sum is formed
+ * on `stream` after both (fp32 accumulation throughout, one rounding to
+ * fp16).  k == 0 uses `stream` only and equals the plain quantised GEMV. */
+int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
+                const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
+                const void* R_pinned, const void* R_scales_f16_dev,
+                int32_t k, void* y_f16_dev, decdec_ws* ws, void* stream);
+
+/* Same with the selection supplied by the caller (layers that share one x,
+ * such as q/k/v or gate/up, select once): idx_dev int32 [k] ascending,
+ * xsel_f16_dev fp16 [k] = x[idx].  Indices must lie in [0, K). */
+int decdec_gemv_idx(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
+                    const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
+                    const void* R_pinned, const void* R_scales_f16_dev,
+                    int32_t k, const int32_t* idx_dev, const void* xsel_f16_dev,
+                    void* y_f16_dev, decdec_ws* ws, void* stream);
+
+/* ------------------------------------------------ offline, on the device */
+
+/* Uniform min/max group-128 quantiser on the GPU (offline preparation; the
+ * paper takes this step from third-party work, Section 5.2):
+ *   s = fp16((max - min) / (2^b - 1)) (1 if 0), z = clip(rint(-min / s), 0, 2^b-1),
+ *   q = clip(rint(w / s) + z, 0, 2^b-1), every operation in IEEE fp32;
+ *   R = fp16(w - s (q - z)).
+ *   W_f32_dev dev fp32 [K][N] in;  Wq_out_dev packed codes out;
+ *   scales/zeros dev fp16 [K/128][N] out;  R_f16_out dev or pinned fp16 [K][N]
+ *   out, or NULL. */
+int decdec_quantize_uniform(const decdec_desc* d, const void* W_f32_dev, void* Wq_out_dev,
+                            void* scales_f16_out_dev, void* zeros_f16_out_dev,
+                            void* R_f16_out, void* stream);
+
+/* ------------------------------------------------------------ diagnostics */
+const char* decdec_strerror(int status);
+int decdec_last_hip_error(void); /* hipError_t of the last failing HIP call on this thread */
+/* DECDEC_OK if p is GPU-visible host memory, DECDEC_ENOTPINNED otherwise. */
+int decdec_check_pinned(const void* p);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DECDEC_H */

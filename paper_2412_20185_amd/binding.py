@@ -1,0 +1,205 @@
+"""ctypes binding of libdecdec.so: argument marshalling only.
+
+Tensors are passed as raw pointers (`tensor.data_ptr()`); the stream is
+torch's current HIP stream unless given.  No step of the hot path is computed
+here.  Loading fails loudly if the library has not been built
+(`python -m paper_2412_20185_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_HERE, "libdecdec.so")
+
+W_UNIFORM_G128, W_LUT_COL8 = 0, 1
+R_FP16, R_INT4_SYM_COL = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
+    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
+    "decdec_pack_residual_int4", "decdec_select_topk", "decdec_gemv", "decdec_gemv_idx",
+    "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
+)
+
+
+class DecdecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().decdec_strerror(status).decode()
+        extra = f" (hipError {lib().decdec_last_hip_error()})" if status == -4 else ""
+        super().__init__(f"{where}: {msg}{extra} [{status}]")
+
+
+class Desc(C.Structure):
+    _fields_ = [("K", C.c_int32), ("N", C.c_int32), ("wbits", C.c_int32), ("wfmt", C.c_int32), ("rfmt", C.c_int32)]
+
+    def __init__(self, K, N, wbits, wfmt=W_UNIFORM_G128, rfmt=R_FP16):
+        super().__init__(int(K), int(N), int(wbits), int(wfmt), int(rfmt))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it is missing (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(lib_path):
+        raise ImportError(f"{lib_path} not found: build it with `python -m paper_2412_20185_amd.build` "
+                          "(needs hipcc); there is no CPU fallback")
+    L = C.CDLL(lib_path)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    dp = C.POINTER(Desc)
+    L.decdec_strerror.restype = C.c_char_p
+    L.decdec_strerror.argtypes = [C.c_int]
+    L.decdec_last_hip_error.restype = C.c_int
+    L.decdec_sc_buffer_bytes.restype = sz
+    L.decdec_sc_buffer_bytes.argtypes = [i32]
+    L.decdec_check_pinned.argtypes = [vp]
+    L.decdec_ws_create.argtypes = [i32, i32, i32, C.POINTER(vp)]
+    L.decdec_ws_destroy.argtypes = [vp]
+    L.decdec_ws_last_selection.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+    L.decdec_ws_read_selection.argtypes = [vp, i32, vp, vp]
+    L.decdec_ws_set_fetch_split.argtypes = [vp, i32]
+    L.decdec_packed_bytes.restype = sz
+    L.decdec_packed_bytes.argtypes = [dp]
+    L.decdec_pack_weights.argtypes = [dp, vp, vp]
+    L.decdec_unpack_weights.argtypes = [dp, vp, vp]
+    L.decdec_pack_residual_int4.argtypes = [i32, i32, vp, vp]
+    L.decdec_select_topk.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.decdec_gemv.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    L.decdec_gemv_idx.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    L.decdec_quantize_uniform.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise DecdecError(status, where)
+
+
+def _ptr(t) -> int | None:
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        return t.data_ptr()
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return int(t)
+
+
+def _stream(stream) -> int | None:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def decdec_strerror(status: int) -> str:
+    return lib().decdec_strerror(status).decode()
+
+
+def decdec_sc_buffer_bytes(k: int) -> int:
+    return int(lib().decdec_sc_buffer_bytes(k))
+
+
+def decdec_check_pinned(t) -> int:
+    return int(lib().decdec_check_pinned(_ptr(t)))
+
+
+class Workspace:
+    """Owns a decdec_ws (side stream, events, selection and partial buffers)."""
+
+    def __init__(self, maxK: int, maxN: int, maxk: int):
+        h = C.c_void_p()
+        _check(lib().decdec_ws_create(maxK, maxN, maxk, C.byref(h)), "decdec_ws_create")
+        self.handle = h
+        self.maxK, self.maxN, self.maxk = maxK, maxN, maxk
+
+    def set_fetch_split(self, row_split: int):
+        _check(lib().decdec_ws_set_fetch_split(self.handle, row_split), "decdec_ws_set_fetch_split")
+
+    def last_selection_ptrs(self):
+        a, b = C.c_void_p(), C.c_void_p()
+        _check(lib().decdec_ws_last_selection(self.handle, C.byref(a), C.byref(b)), "decdec_ws_last_selection")
+        return a.value, b.value
+
+    def read_selection(self, k: int):
+        """Synchronous: (idx int32 [k], xsel fp16 [k]) of the last decdec_gemv on this workspace."""
+        idx = np.empty(k, dtype=np.int32)
+        xs = np.empty(k, dtype=np.float16)
+        _check(lib().decdec_ws_read_selection(self.handle, k, idx.ctypes.data, xs.ctypes.data),
+               "decdec_ws_read_selection")
+        return idx, xs
+
+    def close(self):
+        if self.handle is not None and self.handle.value:
+            lib().decdec_ws_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def decdec_packed_bytes(desc: Desc) -> int:
+    return int(lib().decdec_packed_bytes(C.byref(desc)))
+
+
+def decdec_pack_weights(desc: Desc, codes_KN: np.ndarray) -> np.ndarray:
+    """Host: uint8 codes [K][N] -> packed bytes (np.uint8) in the private layout."""
+    codes = np.ascontiguousarray(codes_KN, dtype=np.uint8)
+    if codes.shape != (desc.K, desc.N):
+        raise ValueError("codes shape must be (K, N)")
+    out = np.empty(decdec_packed_bytes(desc), dtype=np.uint8)
+    _check(lib().decdec_pack_weights(C.byref(desc), codes.ctypes.data, out.ctypes.data), "decdec_pack_weights")
+    return out
+
+
+def decdec_unpack_weights(desc: Desc, packed: np.ndarray) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    if packed.size != decdec_packed_bytes(desc):
+        raise ValueError("packed size mismatch")
+    out = np.empty((desc.K, desc.N), dtype=np.uint8)
+    _check(lib().decdec_unpack_weights(C.byref(desc), packed.ctypes.data, out.ctypes.data), "decdec_unpack_weights")
+    return out
+
+
+def decdec_pack_residual_int4(codes_KN: np.ndarray) -> np.ndarray:
+    codes = np.ascontiguousarray(codes_KN, dtype=np.int8)
+    K, N = codes.shape
+    out = np.empty((K, N // 2), dtype=np.uint8)
+    _check(lib().decdec_pack_residual_int4(K, N, codes.ctypes.data, out.ctypes.data), "decdec_pack_residual_int4")
+    return out
+
+
+def decdec_select_topk(x, K: int, k: int, idx_out, xsel_out=None, stream=None):
+    _check(lib().decdec_select_topk(_ptr(x), K, k, _ptr(idx_out), _ptr(xsel_out), _stream(stream)),
+           "decdec_select_topk")
+
+
+def decdec_gemv(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales, k: int, y, ws: Workspace, stream=None):
+    _check(lib().decdec_gemv(C.byref(desc), _ptr(x), _ptr(Wq), _ptr(scales), _ptr(zeros_or_lut), _ptr(R_pinned),
+                             _ptr(R_scales), k, _ptr(y), ws.handle, _stream(stream)), "decdec_gemv")
+
+
+def decdec_gemv_idx(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales, k: int, idx, xsel, y,
+                    ws: Workspace, stream=None):
+    _check(lib().decdec_gemv_idx(C.byref(desc), _ptr(x), _ptr(Wq), _ptr(scales), _ptr(zeros_or_lut), _ptr(R_pinned),
+                                 _ptr(R_scales), k, _ptr(idx), _ptr(xsel), _ptr(y), ws.handle, _stream(stream)),
+           "decdec_gemv_idx")
+
+
+def decdec_quantize_uniform(desc: Desc, W_f32, Wq_out, scales_out, zeros_out, R_out=None, stream=None):
+    _check(lib().decdec_quantize_uniform(C.byref(desc), _ptr(W_f32), _ptr(Wq_out), _ptr(scales_out),
+                                         _ptr(zeros_out), _ptr(R_out), _stream(stream)), "decdec_quantize_uniform")

@@ -1,0 +1,329 @@
+// C ABI of the library (see include/decdec.h): argument checking, the host
+// helpers that convert plain code matrices to the private packed layout, and
+// the stream choreography of one compensated GEMV.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "../../include/decdec.h"
+#include "kernels.h"
+#include "layout.h"
+
+using namespace decdec;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();  // clear the sticky per-thread error
+    return DECDEC_EHIP;
+}
+#define DD_HIP(call)                               \
+    do {                                           \
+        hipError_t e_ = (call);                    \
+        if (e_ != hipSuccess) return hip_fail(e_); \
+    } while (0)
+
+int pack_kind(const decdec_desc* d) {
+    if (d->wfmt == DECDEC_W_UNIFORM_G128) {
+        if (d->wbits == 4) return PACK_U4;
+        if (d->wbits == 3) return PACK_U3;
+        return -1;
+    }
+    if (d->wfmt == DECDEC_W_LUT_COL8) return d->wbits == 3 ? PACK_LUT3 : -1;
+    return -1;
+}
+
+int check_desc(const decdec_desc* d) {
+    if (d == nullptr) return DECDEC_EINVAL;
+    if (d->K <= 0 || d->N <= 0 || d->K % kGroup != 0 || d->N % kTileCols != 0) return DECDEC_EINVAL;
+    if (d->wfmt != DECDEC_W_UNIFORM_G128 && d->wfmt != DECDEC_W_LUT_COL8) return DECDEC_EINVAL;
+    if (d->rfmt != DECDEC_R_FP16 && d->rfmt != DECDEC_R_INT4_SYM_COL) return DECDEC_EINVAL;
+    if (d->wbits != 3 && d->wbits != 4) return DECDEC_EINVAL;
+    if (pack_kind(d) < 0) return DECDEC_EUNSUPPORTED;
+    return DECDEC_OK;
+}
+
+constexpr int kPinnedCache = 16;
+
+}  // namespace
+
+struct decdec_ws {
+    int32_t maxK, maxN, maxk;
+    int32_t fetch_split;
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_join;
+    int32_t* idx;    // [maxk]
+    void* xsel;      // fp16 [maxk]
+    float* gpart;    // [kMaxGemvSlices][maxN]
+    float* cpart;    // [kMaxFetchSlices][maxN]
+    const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
+    int pinned_n;
+};
+
+extern "C" {
+
+const char* decdec_strerror(int status) {
+    switch (status) {
+        case DECDEC_OK: return "ok";
+        case DECDEC_EINVAL: return "invalid argument";
+        case DECDEC_EUNSUPPORTED: return "unsupported format";
+        case DECDEC_ENOTPINNED: return "residual pointer is not GPU-visible pinned host memory";
+        case DECDEC_EHIP: return "HIP runtime error";
+        case DECDEC_ENOMEM: return "out of memory";
+        default: return "unknown status";
+    }
+}
+
+int decdec_last_hip_error(void) { return g_last_hip_error; }
+
+size_t decdec_sc_buffer_bytes(int32_t k) { return k > 0 ? (size_t)k * (4 + 2) : 0; }
+
+int decdec_check_pinned(const void* p) {
+    if (p == nullptr) return DECDEC_EINVAL;
+    hipPointerAttribute_t at;
+    std::memset(&at, 0, sizeof(at));
+    const hipError_t e = hipPointerGetAttributes(&at, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return DECDEC_ENOTPINNED;
+    }
+    return at.type == hipMemoryTypeHost ? DECDEC_OK : DECDEC_ENOTPINNED;
+}
+
+int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) {
+    if (out == nullptr) return DECDEC_EINVAL;
+    *out = nullptr;
+    if (maxK <= 0 || maxN <= 0 || maxk < 0 || maxk > maxK || maxK > kSelectMaxK) return DECDEC_EINVAL;
+    decdec_ws* ws = new (std::nothrow) decdec_ws();
+    if (ws == nullptr) return DECDEC_ENOMEM;
+    std::memset(ws, 0, sizeof(*ws));
+    ws->maxK = maxK;
+    ws->maxN = maxN;
+    ws->maxk = maxk;
+    const size_t kk = maxk > 0 ? (size_t)maxk : 1;
+    hipError_t e = hipStreamCreateWithFlags(&ws->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ws->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ws->ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->idx), kk * 4);
+    if (e == hipSuccess) e = hipMalloc(&ws->xsel, kk * 2);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->gpart), (size_t)kMaxGemvSlices * maxN * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->cpart), (size_t)kMaxFetchSlices * maxN * 4);
+    if (e != hipSuccess) {
+        const int rc = e == hipErrorOutOfMemory ? DECDEC_ENOMEM : hip_fail(e);
+        (void)hipGetLastError();
+        decdec_ws_destroy(ws);
+        return rc;
+    }
+    *out = ws;
+    return DECDEC_OK;
+}
+
+int decdec_ws_destroy(decdec_ws* ws) {
+    if (ws == nullptr) return DECDEC_OK;
+    if (ws->side) {
+        (void)hipStreamSynchronize(ws->side);
+        (void)hipStreamDestroy(ws->side);
+    }
+    if (ws->ev_fork) (void)hipEventDestroy(ws->ev_fork);
+    if (ws->ev_join) (void)hipEventDestroy(ws->ev_join);
+    if (ws->idx) (void)hipFree(ws->idx);
+    if (ws->xsel) (void)hipFree(ws->xsel);
+    if (ws->gpart) (void)hipFree(ws->gpart);
+    if (ws->cpart) (void)hipFree(ws->cpart);
+    delete ws;
+    return DECDEC_OK;
+}
+
+int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const void** xsel_f16_dev) {
+    if (ws == nullptr) return DECDEC_EINVAL;
+    if (idx_dev) *idx_dev = ws->idx;
+    if (xsel_f16_dev) *xsel_f16_dev = ws->xsel;
+    return DECDEC_OK;
+}
+
+int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, void* xsel_f16_host) {
+    if (ws == nullptr || k < 0 || k > ws->maxk) return DECDEC_EINVAL;
+    DD_HIP(hipStreamSynchronize(ws->side));
+    if (k == 0) return DECDEC_OK;
+    if (idx_host) DD_HIP(hipMemcpy(idx_host, ws->idx, (size_t)k * 4, hipMemcpyDeviceToHost));
+    if (xsel_f16_host) DD_HIP(hipMemcpy(xsel_f16_host, ws->xsel, (size_t)k * 2, hipMemcpyDeviceToHost));
+    return DECDEC_OK;
+}
+
+int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split) {
+    if (ws == nullptr || row_split < 0 || row_split > kMaxFetchSlices) return DECDEC_EINVAL;
+    ws->fetch_split = row_split;
+    return DECDEC_OK;
+}
+
+// ------------------------------------------------------------ host helpers
+
+size_t decdec_packed_bytes(const decdec_desc* d) {
+    if (check_desc(d) != DECDEC_OK) return 0;
+    return (size_t)(d->N / kTileCols) * (size_t)(d->K / kGroup) * (size_t)tile_bytes(pack_kind(d));
+}
+
+int decdec_pack_weights(const decdec_desc* d, const uint8_t* codes_KN, void* out_packed) {
+    const int rc = check_desc(d);
+    if (rc != DECDEC_OK) return rc;
+    if (codes_KN == nullptr || out_packed == nullptr) return DECDEC_EINVAL;
+    const int kind = pack_kind(d), G = d->K / kGroup, NT = d->N / kTileCols;
+    const uint32_t limit = 1u << d->wbits;
+    uint8_t* out = static_cast<uint8_t*>(out_packed);
+    std::memset(out, 0, decdec_packed_bytes(d));
+    for (int nt = 0; nt < NT; ++nt) {
+        for (int g = 0; g < G; ++g) {
+            uint8_t* tile = out + ((size_t)nt * G + g) * tile_bytes(kind);
+            for (int kl = 0; kl < kGroup; ++kl) {
+                const CodeSlot slot = code_slot(kind, kl);
+                const uint8_t* row = codes_KN + ((size_t)g * kGroup + kl) * d->N + (size_t)nt * kTileCols;
+                for (int lane = 0; lane < kTileCols; ++lane) {
+                    const uint32_t q = row[lane];
+                    if (q >= limit) return DECDEC_EINVAL;
+                    for (int r = 0; r < slot.nruns; ++r) {
+                        const BitRun br = slot.run[r];
+                        uint32_t w;
+                        uint8_t* p = tile + word_offset_in_tile(br.word, lane);
+                        std::memcpy(&w, p, 4);
+                        w |= ((q >> br.code_bit) & ((1u << br.nbits) - 1u)) << br.bit;
+                        std::memcpy(p, &w, 4);
+                    }
+                }
+            }
+        }
+    }
+    return DECDEC_OK;
+}
+
+int decdec_unpack_weights(const decdec_desc* d, const void* packed, uint8_t* codes_KN) {
+    const int rc = check_desc(d);
+    if (rc != DECDEC_OK) return rc;
+    if (codes_KN == nullptr || packed == nullptr) return DECDEC_EINVAL;
+    const int kind = pack_kind(d), G = d->K / kGroup, NT = d->N / kTileCols;
+    const uint8_t* in = static_cast<const uint8_t*>(packed);
+    for (int nt = 0; nt < NT; ++nt) {
+        for (int g = 0; g < G; ++g) {
+            const uint8_t* tile = in + ((size_t)nt * G + g) * tile_bytes(kind);
+            for (int kl = 0; kl < kGroup; ++kl) {
+                const CodeSlot slot = code_slot(kind, kl);
+                uint8_t* row = codes_KN + ((size_t)g * kGroup + kl) * d->N + (size_t)nt * kTileCols;
+                for (int lane = 0; lane < kTileCols; ++lane) {
+                    uint32_t q = 0;
+                    for (int r = 0; r < slot.nruns; ++r) {
+                        const BitRun br = slot.run[r];
+                        uint32_t w;
+                        std::memcpy(&w, tile + word_offset_in_tile(br.word, lane), 4);
+                        q |= ((w >> br.bit) & ((1u << br.nbits) - 1u)) << br.code_bit;
+                    }
+                    row[lane] = (uint8_t)q;
+                }
+            }
+        }
+    }
+    return DECDEC_OK;
+}
+
+int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint8_t* out) {
+    if (K <= 0 || N <= 0 || N % 32 != 0 || codes_KN == nullptr || out == nullptr) return DECDEC_EINVAL;
+    for (size_t r = 0; r < (size_t)K; ++r) {
+        for (size_t j = 0; j < (size_t)N / 2; ++j) {
+            const int a = codes_KN[r * N + 2 * j], b = codes_KN[r * N + 2 * j + 1];
+            if (a < -7 || a > 7 || b < -7 || b > 7) return DECDEC_EINVAL;
+            out[r * (N / 2) + j] = (uint8_t)((a & 0xF) | ((b & 0xF) << 4));
+        }
+    }
+    return DECDEC_OK;
+}
+
+// ---------------------------------------------------------------- hot path
+
+int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k, int32_t* idx_out_dev, void* xsel_f16_dev,
+                       void* stream) {
+    if (x_f16_dev == nullptr || K < 8 || K % 8 != 0 || K > kSelectMaxK || k < 0 || k > K) return DECDEC_EINVAL;
+    if (k == 0) return DECDEC_OK;
+    if (idx_out_dev == nullptr) return DECDEC_EINVAL;
+    DD_HIP(launch_select_topk(x_f16_dev, K, k, idx_out_dev, xsel_f16_dev, static_cast<hipStream_t>(stream)));
+    return DECDEC_OK;
+}
+
+static int gemv_common(const decdec_desc* d, const void* x, const void* Wq, const void* scales,
+                       const void* zeros_or_lut, const void* R_pinned, const void* R_scales, int32_t k,
+                       const int32_t* idx_in, const void* xsel_in, bool have_idx, void* y, decdec_ws* ws,
+                       void* stream_v) {
+    const int rc = check_desc(d);
+    if (rc != DECDEC_OK) return rc;
+    if (ws == nullptr || x == nullptr || Wq == nullptr || zeros_or_lut == nullptr || y == nullptr)
+        return DECDEC_EINVAL;
+    if (d->wfmt == DECDEC_W_UNIFORM_G128 && scales == nullptr) return DECDEC_EINVAL;
+    if (d->K > ws->maxK || d->N > ws->maxN || k < 0 || k > d->K || k > ws->maxk) return DECDEC_EINVAL;
+    if (k > 0) {
+        if (R_pinned == nullptr) return DECDEC_EINVAL;
+        if (d->rfmt == DECDEC_R_INT4_SYM_COL && R_scales == nullptr) return DECDEC_EINVAL;
+        if (have_idx && (idx_in == nullptr || xsel_in == nullptr)) return DECDEC_EINVAL;
+        bool known = false;
+        for (int i = 0; i < ws->pinned_n; ++i) known = known || ws->pinned_ok[i] == R_pinned;
+        if (!known) {
+            const int prc = decdec_check_pinned(R_pinned);
+            if (prc != DECDEC_OK) return prc;
+            ws->pinned_ok[ws->pinned_n % kPinnedCache] = R_pinned;
+            if (ws->pinned_n < kPinnedCache) ++ws->pinned_n;
+        }
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const int kind = pack_kind(d);
+
+    int cslices = 0;
+    if (k > 0) {
+        // Section 4.1: all compensation steps run beside the base GEMV on another stream.
+        DD_HIP(hipEventRecord(ws->ev_fork, stream));
+        DD_HIP(hipStreamWaitEvent(ws->side, ws->ev_fork, 0));
+        const int32_t* idx = idx_in;
+        const void* xsel = xsel_in;
+        if (!have_idx) {
+            DD_HIP(launch_select_topk(x, d->K, k, ws->idx, ws->xsel, ws->side));
+            idx = ws->idx;
+            xsel = ws->xsel;
+        }
+        cslices = fetch_slices(d->rfmt, d->N, k, ws->fetch_split);
+        DD_HIP(launch_fetch(d->rfmt, R_pinned, R_scales, idx, xsel, k, d->K, d->N, ws->cpart, cslices, ws->side));
+        DD_HIP(hipEventRecord(ws->ev_join, ws->side));
+    }
+    int gslices = 0;
+    DD_HIP(launch_gemv(kind, Wq, scales, zeros_or_lut, x, ws->gpart, d->K, d->N, &gslices, stream));
+    if (k > 0) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
+    DD_HIP(launch_accumulate(ws->gpart, gslices, ws->cpart, cslices, d->N, y, stream));
+    return DECDEC_OK;
+}
+
+int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
+                const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev, int32_t k,
+                void* y_f16_dev, decdec_ws* ws, void* stream) {
+    return gemv_common(d, x_f16_dev, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, k,
+                       nullptr, nullptr, false, y_f16_dev, ws, stream);
+}
+
+int decdec_gemv_idx(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
+                    const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev, int32_t k,
+                    const int32_t* idx_dev, const void* xsel_f16_dev, void* y_f16_dev, decdec_ws* ws, void* stream) {
+    return gemv_common(d, x_f16_dev, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, k,
+                       idx_dev, xsel_f16_dev, true, y_f16_dev, ws, stream);
+}
+
+int decdec_quantize_uniform(const decdec_desc* d, const void* W_f32_dev, void* Wq_out_dev, void* scales_f16_out_dev,
+                            void* zeros_f16_out_dev, void* R_f16_out, void* stream) {
+    const int rc = check_desc(d);
+    if (rc != DECDEC_OK) return rc;
+    if (d->wfmt != DECDEC_W_UNIFORM_G128) return DECDEC_EUNSUPPORTED;
+    if (W_f32_dev == nullptr || Wq_out_dev == nullptr || scales_f16_out_dev == nullptr ||
+        zeros_f16_out_dev == nullptr)
+        return DECDEC_EINVAL;
+    DD_HIP(launch_quantize_uniform(d->wbits, static_cast<const float*>(W_f32_dev), Wq_out_dev, scales_f16_out_dev,
+                                   zeros_f16_out_dev, R_f16_out, d->K, d->N, static_cast<hipStream_t>(stream)));
+    return DECDEC_OK;
+}
+
+}  // extern "C"

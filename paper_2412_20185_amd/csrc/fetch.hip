@@ -1,0 +1,182 @@
+// Steps 2 and 3 of dynamic error compensation (DecDEC Section 4.1): fetch the
+// residual rows of the selected input channels from pinned CPU memory and
+// multiply them with x[sc_indices]:  o_dec[n] = sum_j R_hat[s_j][n] * x[s_j].
+//
+// Zero-copy (Section 4.3): the kernel reads the rows in place over the host
+// link with plain 128-bit loads; a wavefront covers 1 KiB of one row per load,
+// so requests are cache-line sized and contiguous per row (Section 4.2: each
+// input-channel row is contiguous in CPU memory).  As in the paper's kernel
+// (Section 4.3 "Kernel Fusion") a wave owns a column segment of the rows it
+// handles, so the sum over its rows needs no cross-lane reduction.  Unlike the
+// paper's kernel the rows are additionally split into `slices` (the knob that
+// plays the role of n_tb in Section 4.4: enough requests in flight to fill
+// the link without taking compute units from the base GEMV); each slice
+// writes one fp32 partial row and the accumulate kernel adds them.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace decdec {
+namespace {
+
+constexpr int kUnroll = 4;  // row loads in flight per lane
+
+__device__ __forceinline__ float h2f(uint32_t bits16) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+}
+
+// Wave task (wc, rs): columns [wc*512, wc*512+512) of the rows j in slice rs.
+__global__ __launch_bounds__(256) void fetch_fp16_kernel(const uint4* __restrict__ R,
+                                                        const int32_t* __restrict__ idx,
+                                                        const uint16_t* __restrict__ xsel, int k, int K, int N,
+                                                        float* __restrict__ cpart, int wavecols, int slices) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int task = blockIdx.x * 4 + wave;
+    if (task >= wavecols * slices) return;
+    const int rs = task / wavecols, wc = task - rs * wavecols;
+    const int oct = wc * 64 + lane;  // 8 columns = one 16-byte piece of a row
+    const bool active = oct * 8 < N;
+    const int rows_per = (k + slices - 1) / slices;
+    const int j0 = rs * rows_per, j1 = min(j0 + rows_per, k);
+    const size_t row16 = (size_t)(N / 8);
+
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = j0; j < j1; j += kUnroll) {
+        uint4 v[kUnroll];
+        float xs[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            v[u] = make_uint4(0, 0, 0, 0);
+            xs[u] = 0.f;
+            if (j + u < j1) {
+                const int row = idx[j + u];
+                if (active && (unsigned)row < (unsigned)K) {
+                    v[u] = R[(size_t)row * row16 + oct];
+                    xs[u] = h2f(xsel[j + u]);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc[2 * c] = fmaf(h2f(w[c] & 0xFFFFu), xs[u], acc[2 * c]);
+                acc[2 * c + 1] = fmaf(h2f(w[c] >> 16), xs[u], acc[2 * c + 1]);
+            }
+        }
+    }
+    if (active) {
+        float4* out = reinterpret_cast<float4*>(cpart + (size_t)rs * N + (size_t)oct * 8);
+        out[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+}
+
+// 4-bit residuals (Section 4.2): a 16-byte piece holds 32 columns; a wave
+// covers 2048 columns.  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
+__global__ __launch_bounds__(256) void fetch_int4_kernel(const uint4* __restrict__ R,
+                                                        const uint16_t* __restrict__ Rs,
+                                                        const int32_t* __restrict__ idx,
+                                                        const uint16_t* __restrict__ xsel, int k, int K, int N,
+                                                        float* __restrict__ cpart, int wavecols, int slices) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int task = blockIdx.x * 4 + wave;
+    if (task >= wavecols * slices) return;
+    const int rs = task / wavecols, wc = task - rs * wavecols;
+    const int piece = wc * 64 + lane;  // 32 columns
+    const bool active = piece * 32 < N;
+    const int rows_per = (k + slices - 1) / slices;
+    const int j0 = rs * rows_per, j1 = min(j0 + rows_per, k);
+    const size_t row16 = (size_t)(N / 32);
+
+    float acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
+    for (int j = j0; j < j1; j += kUnroll) {
+        uint4 v[kUnroll];
+        float xs[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            v[u] = make_uint4(0, 0, 0, 0);
+            xs[u] = 0.f;
+            if (j + u < j1) {
+                const int row = idx[j + u];
+                if (active && (unsigned)row < (unsigned)K) {
+                    v[u] = R[(size_t)row * row16 + piece];
+                    xs[u] = h2f(xsel[j + u]);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int q = (int)(w[c] << (28 - 4 * i)) >> 28;  // 4-bit two's complement
+                    acc[8 * c + i] = fmaf((float)q, xs[u], acc[8 * c + i]);
+                }
+            }
+        }
+    }
+    if (active) {
+        const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * 32);
+        float4* out = reinterpret_cast<float4*>(cpart + (size_t)rs * N + (size_t)piece * 32);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint4 sv = s4[b];
+            const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w};
+            float r[8];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                r[2 * c] = acc[8 * b + 2 * c] * h2f(sw[c] & 0xFFFFu);
+                r[2 * c + 1] = acc[8 * b + 2 * c + 1] * h2f(sw[c] >> 16);
+            }
+            out[2 * b] = make_float4(r[0], r[1], r[2], r[3]);
+            out[2 * b + 1] = make_float4(r[4], r[5], r[6], r[7]);
+        }
+    }
+}
+
+inline int cols_per_wave(int rfmt) { return rfmt == 0 ? 512 : 2048; }
+
+}  // namespace
+
+int fetch_slices(int rfmt, int N, int k, int row_split) {
+    const int wavecols = (N + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
+    int slices;
+    if (row_split > 0) {
+        slices = row_split;
+    } else {
+        // about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight
+        slices = (128 + wavecols - 1) / wavecols;
+    }
+    if (slices > k) slices = k;
+    if (slices > kMaxFetchSlices) slices = kMaxFetchSlices;
+    if (slices < 1) slices = 1;
+    return slices;
+}
+
+hipError_t launch_fetch(int rfmt, const void* R_pinned, const void* R_scales, const int32_t* idx, const void* xsel,
+                        int k, int K, int N, float* cpart, int slices, hipStream_t stream) {
+    const int wavecols = (N + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
+    const int tasks = wavecols * slices;
+    const dim3 grid((unsigned)((tasks + 3) / 4)), block(256);
+    if (rfmt == 0) {
+        fetch_fp16_kernel<<<grid, block, 0, stream>>>(static_cast<const uint4*>(R_pinned), idx,
+                                                      static_cast<const uint16_t*>(xsel), k, K, N, cpart, wavecols,
+                                                      slices);
+    } else {
+        fetch_int4_kernel<<<grid, block, 0, stream>>>(static_cast<const uint4*>(R_pinned),
+                                                      static_cast<const uint16_t*>(R_scales), idx,
+                                                      static_cast<const uint16_t*>(xsel), k, K, N, cpart, wavecols,
+                                                      slices);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace decdec

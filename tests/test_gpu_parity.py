@@ -1,0 +1,84 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle, element
+by element, on the same seeded inputs.  Indices bit-exact, y within 2e-3."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+import paper_2412_20185_amd as dd
+from helpers import Problem, assert_parity, TOL_Y
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ws():
+    w = dd.Workspace(28672, 28672, 28672)
+    yield w
+    w.close()
+
+
+def test_config1_4bit_k32(ws):
+    """BASELINE config 1: 1024x1024, 4-bit group 128, 10 outlier channels x20, k = 32."""
+    c = workloads.config1()
+    p = Problem(c["W"], 4)
+    y_ref, sc = p.reference(c["x"], c["k"])
+    y, idx, xsel = p.run(c["x"], c["k"], ws)
+    err = assert_parity(y, y_ref, idx, sc, what="config1")
+    assert np.array_equal(xsel, c["x"][sc])
+    print(f"config1 rel err {err:.2e}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("K,N", [(1024, 1024), (512, 192), (4096, 1024), (1664, 320)])
+def test_uniform_shapes_and_k(ws, bits, K, N):
+    W = workloads.weights(90 + bits, 0, 0, K, N)
+    p = Problem(W, bits)
+    for step, k in enumerate([0, 1, 7, workloads.k_for_fraction(K, 0.02), K // 3, K]):
+        x = workloads.x_gauss_outliers(90 + bits, 0, 0, step, K)
+        y_ref, sc = p.reference(x, k)
+        y, idx, _ = p.run(x, k, ws)
+        assert_parity(y, y_ref, idx, sc, what=f"b{bits} {K}x{N} k={k}")
+
+
+def test_k0_equals_plain_quantised_gemv_and_kK_recovers_full_precision(ws):
+    c = workloads.config1()
+    p = Problem(c["W"], 4)
+    x = c["x"]
+    y0, _, _ = p.run(x, 0, ws)
+    plain = p.W_hat.T @ x.astype(np.float64)
+    assert oracle.error_metric(y0.astype(np.float64), plain) <= TOL_Y
+    yK, idx, _ = p.run(x, p.K, ws)
+    assert np.array_equal(idx, np.arange(p.K))
+    xd = x.astype(np.float64)
+    full = c["W"].astype(np.float64).T @ xd
+    # only the fp16 rounding of the stored residual separates the k = K result from W x
+    r_bound = 2.0 ** -11 * (np.abs(p.R.astype(np.float64)).T @ np.abs(xd))
+    rms = np.sqrt(np.mean(full ** 2))
+    assert np.all(np.abs(yK.astype(np.float64) - full) <= r_bound + TOL_Y * np.maximum(np.abs(full), 0.01 * rms))
+
+
+def test_all_integer_case_is_bit_exact(ws):
+    """s = 1, z = 0, small-integer x and R: every partial sum is an integer below
+    2^24, so fp32 accumulation in any order must reproduce the oracle exactly."""
+    g = np.random.default_rng(1)
+    for bits in (4, 3):
+        K, N = 1024, 256
+        p = Problem.__new__(Problem)
+        p.K, p.N, p.bits = K, N, bits
+        p.codes = g.integers(0, 2 ** bits, size=(K, N)).astype(np.uint8)
+        p.scales = np.ones((K // 128, N), np.float16)
+        p.zeros = g.integers(0, 2 ** bits, size=(K // 128, N)).astype(np.float16)
+        p.lut = None
+        p.R = g.integers(-3, 4, size=(K, N)).astype(np.float16)
+        p.R_real, p.Rq, p.Rs, p.rfmt = p.R, None, None, "fp16"
+        p.desc = dd.Desc(K, N, bits)
+        p.W_hat = oracle.dequantize_uniform(p.codes, p.scales, p.zeros)
+        p._dev = None
+        x = g.integers(-4, 5, size=K).astype(np.float16)
+        y_ref, sc = p.reference(x, 64)
+        y, idx, _ = p.run(x, 64, ws)
+        assert np.array_equal(idx, sc)
+        assert np.abs(y_ref).max() < 2048          # exactly representable in fp16
+        assert np.array_equal(y.astype(np.float64), y_ref)
