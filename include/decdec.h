@@ -105,6 +105,24 @@ int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, 
  * choice.  Affects later calls on this workspace. */
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
 
+/* Number of 128-channel groups each wavefront of the base GEMV walks through
+ * (how finely K is split over the chip); 0 restores the built-in choice. */
+int decdec_ws_set_gemv_split(decdec_ws* ws, int32_t groups_per_wave);
+
+/* Kernel timing for benchmarks.  capacity > 0 allocates that many sets of HIP
+ * events (set-up call: allocates, synchronises) and makes every later
+ * decdec_gemv / decdec_gemv_idx on this workspace record events around its
+ * base-GEMV kernel (on the caller's stream) and around its selection and
+ * residual-fetch kernels (on the side stream); capacity == 0 turns it off and
+ * frees the events.  Calls beyond `capacity` since the last read are not
+ * timed. */
+int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity);
+/* Synchronous: waits for all recorded events, returns the summed elapsed
+ * milliseconds per kernel class and the number of timed calls (calls[0]:
+ * base GEMV, calls[1]: selection, calls[2]: fetch), then starts over.  Any
+ * output pointer may be NULL. */
+int decdec_ws_read_profile(decdec_ws* ws, double* gemv_ms, double* select_ms, double* fetch_ms, int32_t* calls);
+
 /* ------------------------------------------------- host helpers (offline) */
 
 /* Bytes of the library-private packed form of the K x N code matrix. */

@@ -29,7 +29,7 @@ def quantize_uniform(W: np.ndarray, bits: int, group: int = GROUP):
     operation, no fusion) so that an fp32 device implementation can reproduce
     the integer codes exactly:
         s  = fp16(fp32(hi - lo) / (2^b - 1)),  s = 1 if that is 0
-        z  = clip(rint(-lo / s), 0, 2^b - 1)
+        z  = clip(rint(-lo / s), 0, 2^b - 1)      (stored as +0, never -0)
         q  = clip(rint(w / s) + z, 0, 2^b - 1)
     """
     W = np.ascontiguousarray(W, dtype=np.float32)
@@ -44,7 +44,7 @@ def quantize_uniform(W: np.ndarray, bits: int, group: int = GROUP):
     s = s32.astype(np.float16)
     s[s == 0] = np.float16(1.0)
     sf = s.astype(np.float32)
-    z = np.clip(np.rint((-lo / sf).astype(np.float32)), 0, qmax).astype(np.float32)
+    z = (np.clip(np.rint((-lo / sf).astype(np.float32)), 0, qmax) + np.float32(0)).astype(np.float32)  # +0: never -0
     q = np.rint((Wg / sf[:, None, :]).astype(np.float32)) + z[:, None, :]
     q = np.clip(q, 0, qmax)
     return q.astype(np.uint8).reshape(K, N), s, z.astype(np.float16)

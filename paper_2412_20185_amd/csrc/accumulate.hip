@@ -19,8 +19,10 @@ __global__ __launch_bounds__(256) void accumulate_kernel(const float* __restrict
     const int n = blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     float ob = 0.f;
+#pragma unroll 8
     for (int s = 0; s < gslices; ++s) ob += gpart[(size_t)s * N + n];
     float odec = 0.f;
+#pragma unroll 8
     for (int r = 0; r < cslices; ++r) odec += cpart[(size_t)r * N + n];
     y[n] = (_Float16)(ob + odec);
 }

@@ -54,6 +54,7 @@ constexpr int kPinnedCache = 16;
 struct decdec_ws {
     int32_t maxK, maxN, maxk;
     int32_t fetch_split;
+    int32_t gemv_gpw;
     hipStream_t side;
     hipEvent_t ev_fork, ev_join;
     int32_t* idx;    // [maxk]
@@ -62,6 +63,10 @@ struct decdec_ws {
     float* cpart;    // [kMaxFetchSlices][maxN]
     const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
     int pinned_n;
+    // optional kernel timing: per call events g0,g1 (caller's stream) and s0,f0,f1 (side stream)
+    hipEvent_t* prof_ev;   // [prof_cap][5]
+    uint8_t* prof_mask;    // [prof_cap] bit0: gemv timed, bit1: select timed, bit2: fetch timed
+    int32_t prof_cap, prof_used;
 };
 
 extern "C" {
@@ -122,8 +127,85 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
     return DECDEC_OK;
 }
 
+static void free_profiling(decdec_ws* ws) {
+    if (ws->prof_ev) {
+        for (int i = 0; i < ws->prof_cap * 5; ++i)
+            if (ws->prof_ev[i]) (void)hipEventDestroy(ws->prof_ev[i]);
+        delete[] ws->prof_ev;
+        delete[] ws->prof_mask;
+    }
+    ws->prof_ev = nullptr;
+    ws->prof_mask = nullptr;
+    ws->prof_cap = ws->prof_used = 0;
+}
+
+int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity) {
+    if (ws == nullptr || capacity < 0 || capacity > (1 << 20)) return DECDEC_EINVAL;
+    DD_HIP(hipDeviceSynchronize());
+    free_profiling(ws);
+    if (capacity == 0) return DECDEC_OK;
+    ws->prof_ev = new (std::nothrow) hipEvent_t[(size_t)capacity * 5]();
+    ws->prof_mask = new (std::nothrow) uint8_t[capacity]();
+    if (ws->prof_ev == nullptr || ws->prof_mask == nullptr) {
+        delete[] ws->prof_ev;
+        delete[] ws->prof_mask;
+        ws->prof_ev = nullptr;
+        ws->prof_mask = nullptr;
+        return DECDEC_ENOMEM;
+    }
+    ws->prof_cap = capacity;
+    for (int i = 0; i < capacity * 5; ++i) {
+        const hipError_t e = hipEventCreate(&ws->prof_ev[i]);
+        if (e != hipSuccess) {
+            free_profiling(ws);
+            return hip_fail(e);
+        }
+    }
+    return DECDEC_OK;
+}
+
+int decdec_ws_read_profile(decdec_ws* ws, double* gemv_ms, double* select_ms, double* fetch_ms, int32_t* calls) {
+    if (ws == nullptr) return DECDEC_EINVAL;
+    double t[3] = {0, 0, 0};
+    int32_t n[3] = {0, 0, 0};
+    if (ws->prof_ev) {
+        DD_HIP(hipDeviceSynchronize());
+        for (int i = 0; i < ws->prof_used; ++i) {
+            hipEvent_t* ev = ws->prof_ev + (size_t)i * 5;
+            float ms = 0.f;
+            if (ws->prof_mask[i] & 1) {
+                DD_HIP(hipEventElapsedTime(&ms, ev[0], ev[1]));
+                t[0] += ms;
+                ++n[0];
+            }
+            if (ws->prof_mask[i] & 2) {
+                DD_HIP(hipEventElapsedTime(&ms, ev[2], ev[3]));
+                t[1] += ms;
+                ++n[1];
+            }
+            if (ws->prof_mask[i] & 4) {
+                DD_HIP(hipEventElapsedTime(&ms, ev[3], ev[4]));
+                t[2] += ms;
+                ++n[2];
+            }
+            ws->prof_mask[i] = 0;
+        }
+        ws->prof_used = 0;
+    }
+    if (gemv_ms) *gemv_ms = t[0];
+    if (select_ms) *select_ms = t[1];
+    if (fetch_ms) *fetch_ms = t[2];
+    if (calls) {
+        calls[0] = n[0];
+        calls[1] = n[1];
+        calls[2] = n[2];
+    }
+    return DECDEC_OK;
+}
+
 int decdec_ws_destroy(decdec_ws* ws) {
     if (ws == nullptr) return DECDEC_OK;
+    free_profiling(ws);
     if (ws->side) {
         (void)hipStreamSynchronize(ws->side);
         (void)hipStreamDestroy(ws->side);
@@ -142,6 +224,12 @@ int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const
     if (ws == nullptr) return DECDEC_EINVAL;
     if (idx_dev) *idx_dev = ws->idx;
     if (xsel_f16_dev) *xsel_f16_dev = ws->xsel;
+    return DECDEC_OK;
+}
+
+int decdec_ws_set_gemv_split(decdec_ws* ws, int32_t groups_per_wave) {
+    if (ws == nullptr || groups_per_wave < 0 || groups_per_wave > 1024) return DECDEC_EINVAL;
+    ws->gemv_gpw = groups_per_wave;
     return DECDEC_OK;
 }
 
@@ -275,6 +363,13 @@ static int gemv_common(const decdec_desc* d, const void* x, const void* Wq, cons
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const int kind = pack_kind(d);
+    hipEvent_t* pev = nullptr;
+    uint8_t* pmask = nullptr;
+    if (ws->prof_ev != nullptr && ws->prof_used < ws->prof_cap) {
+        pev = ws->prof_ev + (size_t)ws->prof_used * 5;
+        pmask = ws->prof_mask + ws->prof_used;
+        ++ws->prof_used;
+    }
 
     int cslices = 0;
     if (k > 0) {
@@ -284,16 +379,28 @@ static int gemv_common(const decdec_desc* d, const void* x, const void* Wq, cons
         const int32_t* idx = idx_in;
         const void* xsel = xsel_in;
         if (!have_idx) {
+            if (pev) DD_HIP(hipEventRecord(pev[2], ws->side));
             DD_HIP(launch_select_topk(x, d->K, k, ws->idx, ws->xsel, ws->side));
             idx = ws->idx;
             xsel = ws->xsel;
+            if (pev) *pmask |= 2;
         }
+        if (pev) DD_HIP(hipEventRecord(pev[3], ws->side));
         cslices = fetch_slices(d->rfmt, d->N, k, ws->fetch_split);
         DD_HIP(launch_fetch(d->rfmt, R_pinned, R_scales, idx, xsel, k, d->K, d->N, ws->cpart, cslices, ws->side));
+        if (pev) {
+            DD_HIP(hipEventRecord(pev[4], ws->side));
+            *pmask |= 4;
+        }
         DD_HIP(hipEventRecord(ws->ev_join, ws->side));
     }
     int gslices = 0;
-    DD_HIP(launch_gemv(kind, Wq, scales, zeros_or_lut, x, ws->gpart, d->K, d->N, &gslices, stream));
+    if (pev) DD_HIP(hipEventRecord(pev[0], stream));
+    DD_HIP(launch_gemv(kind, Wq, scales, zeros_or_lut, x, ws->gpart, d->K, d->N, ws->gemv_gpw, &gslices, stream));
+    if (pev) {
+        DD_HIP(hipEventRecord(pev[1], stream));
+        *pmask |= 1;
+    }
     if (k > 0) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
     DD_HIP(launch_accumulate(ws->gpart, gslices, ws->cpart, cslices, d->N, y, stream));
     return DECDEC_OK;

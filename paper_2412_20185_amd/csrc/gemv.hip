@@ -151,9 +151,60 @@ __device__ __forceinline__ float group_dot_lut3(const uint4 (&q)[3], const LutTa
 
 constexpr int kWavesPerBlock = 4;
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// 128-bit load of data that is read exactly once (the weight stream).
+__device__ __forceinline__ uint4 load_streaming(const uint4* p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// What one lane holds of one tile while it is in flight.
+template <int KIND>
+struct TileRegs {
+    uint4 q[words_per_lane(KIND) / 4];
+    uint16_t s, z;   // fp16 scale and zero point of (group, column)   (uniform formats)
+    uint32_t xp;     // this lane's activation pair, for the group's sum of x
+};
+
+template <int KIND>
+__device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint4* __restrict__ tile,
+                                          const uint16_t* __restrict__ scales,
+                                          const uint16_t* __restrict__ zeros, const uint32_t* __restrict__ x32,
+                                          int g, int N, int n, int lane) {
+    constexpr int P = words_per_lane(KIND) / 4;
+#pragma unroll
+    for (int p = 0; p < P; ++p) r.q[p] = load_streaming(tile + p * kTileCols);
+    if constexpr (KIND != PACK_LUT3) {
+        r.s = scales[(size_t)g * N + n];
+        r.z = zeros[(size_t)g * N + n];
+        r.xp = x32[g * 64 + lane];
+    }
+}
+
+template <int KIND>
+__device__ __forceinline__ float tile_dot(const TileRegs<KIND>& r, const LutTables& T,
+                                          const uint32_t* __restrict__ xs) {
+    if constexpr (KIND == PACK_LUT3) {
+        return group_dot_lut3(r.q, T, xs);
+    } else {
+        const float gs = wave_sum(dot2(r.xp, 0x3C003C00u, 0.f));  // sum of the group's 128 activations
+        float d;
+        if constexpr (KIND == PACK_U4) {
+            d = group_dot_u4(r.q, xs);
+        } else {
+            d = group_dot_u3(r.q, xs);
+        }
+        const float s = (float)__builtin_bit_cast(_Float16, r.s);
+        const float z = (float)__builtin_bit_cast(_Float16, r.z);
+        return s * (d - z * gs);
+    }
+}
+
 // grid: (N/64) * slices workgroups of 256 threads; workgroup (nt, ks) covers
 // column tile nt and groups [ks*4*gpw, (ks+1)*4*gpw), wave w of it the gpw
-// groups starting at (ks*4 + w)*gpw.  part is fp32 [slices][N].
+// groups starting at (ks*4 + w)*gpw.  part is fp32 [slices][N].  The loads of
+// the next tile are issued before the current one is consumed.
 template <int KIND>
 __global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
                                                   const uint16_t* __restrict__ scales,
@@ -161,6 +212,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
                                                   const uint32_t* __restrict__ x32, float* __restrict__ part,
                                                   int N, int G, int slices, int gpw) {
     constexpr int P = words_per_lane(KIND) / 4;  // 16-byte pieces per lane per tile
+    constexpr int kTileStride = P * kTileCols;   // uint4 per tile
     __shared__ float red[kWavesPerBlock][kTileCols];
 
     const int lane = threadIdx.x & 63;
@@ -178,26 +230,17 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
     }
 
     float total = 0.f;
-    const uint4* tile = Wq + ((size_t)nt * G + g) * (P * kTileCols) + lane;
-    for (; g < g_end; ++g, tile += P * kTileCols) {
-        uint4 q[P];
-#pragma unroll
-        for (int p = 0; p < P; ++p) q[p] = tile[p * kTileCols];
-        const uint32_t* xs = x32 + g * 64;
-        if constexpr (KIND == PACK_LUT3) {
-            total += group_dot_lut3(q, T, xs);
-        } else {
-            const _Float16 s = __builtin_bit_cast(_Float16, scales[(size_t)g * N + n]);
-            const _Float16 z = __builtin_bit_cast(_Float16, zeros_or_lut[(size_t)g * N + n]);
-            const float gs = wave_sum(dot2(x32[g * 64 + lane], 0x3C003C00u, 0.f));
-            float r;
-            if constexpr (KIND == PACK_U4) {
-                r = group_dot_u4(q, xs);
-            } else {
-                r = group_dot_u3(q, xs);
-            }
-            total += (float)s * (r - (float)z * gs);
-        }
+    const uint4* tile = Wq + ((size_t)nt * G + g) * kTileStride + lane;
+    TileRegs<KIND> ra, rb;
+    if (g < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g, N, n, lane);
+    while (g < g_end) {
+        if (g + 1 < g_end) load_tile<KIND>(rb, tile + kTileStride, scales, zeros_or_lut, x32, g + 1, N, n, lane);
+        total += tile_dot<KIND>(ra, T, x32 + g * 64);
+        if (++g >= g_end) break;
+        tile += 2 * kTileStride;
+        if (g + 1 < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g + 1, N, n, lane);
+        total += tile_dot<KIND>(rb, T, x32 + g * 64);
+        ++g;
     }
 
     red[wave][lane] = total;
@@ -212,12 +255,13 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
 
 }  // namespace
 
-int gemv_slices(int N, int G, int* gpw_out) {
-    // Aim for about 4096 resident wavefronts (256 CUs x 16) so that the whole
-    // matrix is requested at once; never more than kMaxGemvSlices partial rows.
+int gemv_slices(int N, int G, int gpw_request, int* gpw_out) {
+    // One group per wavefront while that keeps the grid within what the chip
+    // holds at once (256 CUs x 32 waves): the whole matrix is then requested in
+    // one go.  Larger problems give every wavefront several groups.
     const int tiles = N / kTileCols;
     const long units = (long)tiles * G;
-    int gpw = (int)((units + 4095) / 4096);
+    int gpw = gpw_request > 0 ? gpw_request : (int)((units + 8191) / 8192);
     if (gpw < 1) gpw = 1;
     int per_block = gpw * kWavesPerBlock;
     int slices = (G + per_block - 1) / per_block;
@@ -231,10 +275,10 @@ int gemv_slices(int N, int G, int* gpw_out) {
 }
 
 hipError_t launch_gemv(int kind, const void* Wq, const void* scales, const void* zeros_or_lut, const void* x,
-                       float* part, int K, int N, int* slices_out, hipStream_t stream) {
+                       float* part, int K, int N, int gpw_request, int* slices_out, hipStream_t stream) {
     const int G = K / kGroup;
     int gpw = 1;
-    const int slices = gemv_slices(N, G, &gpw);
+    const int slices = gemv_slices(N, G, gpw_request, &gpw);
     *slices_out = slices;
     const dim3 grid((unsigned)((N / kTileCols) * slices)), block(256);
     const uint4* w = static_cast<const uint4*>(Wq);

@@ -16,8 +16,8 @@ constexpr int kSelectMaxK = 65536;
 // gemv.hip ---------------------------------------------------------------
 // part: fp32 [slices][N]; *slices_out receives the number of rows written.
 hipError_t launch_gemv(int kind, const void* Wq, const void* scales, const void* zeros_or_lut, const void* x,
-                       float* part, int K, int N, int* slices_out, hipStream_t stream);
-int gemv_slices(int N, int G, int* gpw_out);
+                       float* part, int K, int N, int gpw_request, int* slices_out, hipStream_t stream);
+int gemv_slices(int N, int G, int gpw_request, int* gpw_out);
 
 // select.hip -------------------------------------------------------------
 hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream);

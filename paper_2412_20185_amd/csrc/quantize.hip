@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void quantize_uniform_kernel(const float* __re
     _Float16 s16 = (_Float16)((hi - lo) / qmax);
     if (s16 == (_Float16)0.f) s16 = (_Float16)1.f;
     const float s = (float)s16;
-    const float z = fminf(fmaxf(rintf(-lo / s), 0.f), qmax);
+    const float z = fminf(fmaxf(rintf(-lo / s), 0.f), qmax) + 0.f;  // + 0: a zero point is never -0
 
     uint32_t words[words_per_lane(KIND)];
 #pragma unroll

@@ -82,3 +82,62 @@ def test_all_integer_case_is_bit_exact(ws):
         assert np.array_equal(idx, sc)
         assert np.abs(y_ref).max() < 2048          # exactly representable in fp16
         assert np.array_equal(y.astype(np.float64), y_ref)
+
+
+@pytest.mark.parametrize("K,N", [(1024, 1024), (512, 192), (2048, 320)])
+def test_lut3_shapes_and_k(ws, K, N):
+    """Config 4 style: per-column 8-entry codebook, Student-t activations."""
+    W = workloads.weights(40, 0, 0, K, N)
+    p = Problem(W, 3, wfmt="lut", lut_iters=4)
+    for step, k in enumerate([0, 1, workloads.k_for_fraction(K, 0.01), K // 5, K]):
+        x = workloads.x_student_t(4, 0, 0, step, K)
+        y_ref, sc = p.reference(x, k)
+        y, idx, _ = p.run(x, k, ws)
+        assert_parity(y, y_ref, idx, sc, what=f"lut {K}x{N} k={k}")
+
+
+@pytest.mark.parametrize("wfmt,bits", [("uniform", 3), ("uniform", 4), ("lut", 3)])
+@pytest.mark.parametrize("K,N", [(1024, 1024), (640, 192), (1536, 2112)])
+def test_int4_residuals(ws, wfmt, bits, K, N):
+    """Config 5 style: 4-bit symmetric residuals with one scale per output column."""
+    W = workloads.weights(50, 0, 0, K, N)
+    p = Problem(W, bits, wfmt=wfmt, rfmt="int4", lut_iters=2, alphas=oracle.quantize.DEFAULT_ALPHAS[::5])
+    assert p.Rq.min() >= -7 and p.Rq.max() <= 7
+    for step, k in enumerate([1, workloads.k_for_kchunk(K, 15) or 3, K // 2, K]):
+        x = workloads.x_student_t(5, 0, 0, step, K, outlier_frac=0.005, outlier_mult=30.0)
+        y_ref, sc = p.reference(x, k)
+        y, idx, _ = p.run(x, k, ws)
+        assert_parity(y, y_ref, idx, sc, what=f"int4 {wfmt}{bits} {K}x{N} k={k}")
+
+
+def test_caller_supplied_selection_matches_internal_selection(ws):
+    """q/k/v share one x: select once, reuse the indices (decdec_gemv_idx)."""
+    K, N = 2048, 512
+    W = workloads.weights(60, 0, 0, K, N)
+    p = Problem(W, 4)
+    x = workloads.x_gauss_outliers(60, 0, 0, 0, K)
+    k = 41
+    y1, idx, _ = p.run(x, k, ws)
+    y2, _, _ = p.run(x, k, ws, idx=oracle.topk_abs(x, k))
+    assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+    # an arbitrary (not top-k) channel list is honoured as given
+    some = np.sort(np.random.default_rng(0).choice(K, 17, replace=False)).astype(np.int32)
+    y3, _, _ = p.run(x, 17, ws, idx=some)
+    ref = oracle.compensated_gemv(p.W_hat, x, p.R_real, some)
+    assert oracle.error_metric(y3.astype(np.float64), ref) <= TOL_Y
+
+
+def test_repeated_calls_are_bitwise_reproducible(ws):
+    """The accumulate adds partial rows in a fixed order: no run-to-run variation,
+    and nothing left over in the workspace from a previous, larger call."""
+    K, N = 4096, 1024
+    p = Problem(workloads.weights(61, 0, 0, K, N), 3)
+    big = Problem(workloads.weights(62, 0, 0, 1024, 4096), 4)
+    x = workloads.x_gauss_outliers(61, 0, 0, 0, K)
+    xb = workloads.x_gauss_outliers(62, 0, 0, 0, 1024)
+    first, _, _ = p.run(x, 81, ws)
+    for i in range(20):
+        if i % 5 == 0:
+            big.run(xb, 300, ws)
+        y, _, _ = p.run(x, 81, ws)
+        assert np.array_equal(y.view(np.uint16), first.view(np.uint16))

@@ -26,6 +26,7 @@ def brute_uniform(W, bits, group=128):
                 s = np.float16(1)
             sf = f32(s)
             z = min(max(f32(np.rint(f32(-lo / sf))), f32(0)), qmax)
+            z = f32(0) if z == 0 else z          # a zero point is stored as +0, never -0
             for i, w in enumerate(col):
                 q = f32(np.rint(f32(w / sf))) + z
                 codes[g * group + i, n] = int(min(max(q, f32(0)), qmax))
@@ -40,7 +41,7 @@ def check_uniform(qfn):
         W[128:, 1] = 0.0125                       # a constant group -> s = 0 -> 1
         c, s, z = qfn(W, bits)
         bc, bs, bz = brute_uniform(W, bits)
-        if not (np.array_equal(c, bc) and np.array_equal(s, bs) and np.array_equal(z, bz)):
+        if not (np.array_equal(c, bc) and np.array_equal(s, bs) and np.array_equal(z.view(np.uint16), bz.view(np.uint16))):
             return False
         # closed form: weights already on a grid are recovered exactly
         qmax = 2 ** bits - 1
