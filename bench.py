@@ -42,6 +42,10 @@ def main() -> int:
     ap.add_argument("--xpool", type=int, default=32, help="distinct activation draws rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fetch-split", type=int, default=0)
+    ap.add_argument("--graph", type=int, default=1, help="1: replay each distinct step as a captured HIP graph")
+    ap.add_argument("--grouping", choices=("grouped", "separate"), default="grouped",
+                    help="grouped: q/k/v and gate/up (same x) go through one decdec_gemv_multi call each, "
+                         "as the paper's four layer types; separate: seven decdec_gemv calls")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the method has no multi-GPU component); "
@@ -53,7 +57,7 @@ def main() -> int:
 
     import workloads
     import paper_2412_20185_amd as dd
-    from paper_2412_20185_amd.layer import UniformLinear
+    from paper_2412_20185_amd.layer import LinearGroup, UniformLinear
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -77,36 +81,65 @@ def main() -> int:
     ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
     kk = {name: workloads.k_for_fraction(K, K_FRACTION) for name, K, _, _ in shapes}
     maxK = max(K for _, K, _, _ in shapes)
-    maxN = max(N for _, _, N, _ in shapes)
+    maxN = 2 * max(N for _, _, N, _ in shapes)       # room for the concatenated columns of gate + up
     ws = dd.Workspace(maxK, maxN, max(kk.values()))
     if args.fetch_split:
         ws.set_fetch_split(args.fetch_split)
     setup_s = time.time() - t_setup
 
+    # calls per step, in the layer's dependency order: (input name, k, [GEMV names])
+    if args.grouping == "grouped":
+        order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
+    else:
+        order = [(which, [name]) for name, _, _, which in shapes]
+    groups = [[LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for _, names in order]
+              for lins in layers]
+    n_calls = len(order)
+
     def step(i: int, compensate: bool = True):
-        lins = layers[i % args.layers]
         xs = xpool[i % args.xpool]
-        for name, _, _, which in shapes:
-            lins[name].gemv(xs[which], kk[name] if compensate else 0, ys[name], ws)
+        for (which, names), grp in zip(order, groups[i % args.layers]):
+            grp.gemv(xs[which], kk[names[0]] if compensate else 0, ws)
+
+    graphs = {}
+    cap_stream = torch.cuda.Stream() if args.graph else None
+
+    def run_step(i: int, compensate: bool):
+        """One step, eagerly or as a replay of its captured graph."""
+        if not args.graph:
+            step(i, compensate)
+            return
+        import math
+        key = (i % math.lcm(args.layers, args.xpool), compensate)
+        g = graphs.get(key)
+        if g is None:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=cap_stream):
+                step(i, compensate)
+            graphs[key] = g
+        g.replay()
 
     def timed(n: int, compensate: bool) -> float:
+        if args.graph:
+            for i in range(n):          # capture outside the timed region
+                run_step(i, compensate)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(n):
-            step(i, compensate)
+            run_step(i, compensate)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
     # ------------------------------------------------------------ timed region
     for i in range(args.warmup):
-        step(i, True)
+        run_step(i, True)
     ms_step = timed(args.steps, True)
     for i in range(args.warmup):
-        step(i, False)
+        run_step(i, False)
     ms_base = timed(args.steps, False)
 
     # --------------------------------- per-kernel durations over the same steps
-    ws.set_profiling(args.steps * len(shapes))
+    ws.set_profiling(args.steps * n_calls)
     for i in range(args.steps):
         step(i, True)
     prof = ws.read_profile()
@@ -144,6 +177,7 @@ def main() -> int:
                         "weights, fp16 activations with 0.5% outlier channels, fp16 host residuals, k = 2% of K "
                         "(81 / 286)",
             "layers_rotated": args.layers,
+            "gemvs_per_step": len(shapes),
             "weight_bytes_per_step": gemv_bytes,
             "residual_bytes_per_step": fetch_bytes,
             "k": kk,
@@ -151,7 +185,7 @@ def main() -> int:
         "base_only_us_per_gemv": round(ms_base * 1e3 / len(shapes), 3),
         "compensation_added_pct": round((ms_step / ms_base - 1.0) * 100.0, 1),
         "roofline": {
-            "kernel": "gemv_kernel<PACK_U3> (base GEMV, 7 launches per step)",
+            "kernel": f"gemv_kernel<PACK_U3> (base GEMV, {n_calls} launches per step)",
             "bound": "hbm",
             "achieved": round(gemv_gbs, 1),
             "peak": HBM_PEAK_GBS,
@@ -163,7 +197,7 @@ def main() -> int:
             "avg_launch_us_without_compensation": round(gb_ms * 1e3 / max(gb_n, 1), 3),
         },
         "link_roofline": {
-            "kernel": "fetch_fp16_kernel (zero-copy residual fetch + residual GEMV, 7 launches per step)",
+            "kernel": f"fetch_fp16_kernel (zero-copy residual fetch + residual GEMV, {n_calls} launches per step)",
             "bound": "host_link",
             "achieved": round(fetch_gbs, 2),
             "peak": LINK_PEAK_GBS,
@@ -173,6 +207,9 @@ def main() -> int:
         },
         "select_avg_us": round(s_ms * 1e3 / max(s_n, 1), 3),
         "setup_s": round(setup_s, 1),
+        "launch": "hip-graph replay" if args.graph else "eager",
+        "grouping": args.grouping,
+        "calls_per_step": n_calls,
     }
 
     # ---------------------------------------------- oracle: parity + CPU baseline
@@ -185,10 +222,12 @@ def main() -> int:
         # GPU results of step 0 on layer 0, GEMV by GEMV
         gpu = {}
         xs0 = xpool[0]
-        for name, _, _, which in shapes:
-            layers[0][name].gemv(xs0[which], kk[name], ys[name], ws)
+        for (which, names), grp in zip(order, groups[0]):          # the same calls the timed step makes
+            grp.gemv(xs0[which], kk[names[0]], ws)
             torch.cuda.synchronize()
-            gpu[name] = (ys[name].cpu().numpy().astype(np.float64), ws.read_selection(kk[name])[0])
+            sel = ws.read_selection(kk[names[0]])[0]
+            for name in names:
+                gpu[name] = (ys[name].cpu().numpy().astype(np.float64), sel)
         worst, mism, cpu_s = 0.0, 0, 0.0
         import contextlib
         ctx = threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()

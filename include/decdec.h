@@ -179,6 +179,26 @@ int decdec_gemv_idx(const decdec_desc* d, const void* x_f16_dev, const void* Wq_
                     int32_t k, const int32_t* idx_dev, const void* xsel_f16_dev,
                     void* y_f16_dev, decdec_ws* ws, void* stream);
 
+/* One weight matrix with its residual and its output, for decdec_gemv_multi. */
+typedef struct {
+    const decdec_desc* desc;
+    const void* Wq_dev;               /* as in decdec_gemv */
+    const void* scales_f16_dev;
+    const void* zeros_or_lut_f16_dev;
+    const void* R_pinned;
+    const void* R_scales_f16_dev;
+    void* y_f16_dev;                  /* dev fp16 [desc->N] out */
+} decdec_linear;
+
+/* Up to 4 linear layers that consume the same x (q/k/v, gate/up: the paper's
+ * fused layer types of Section 4.4) in one pass: one selection, one launch of
+ * each kernel over the concatenated output columns.  All descriptors must
+ * agree in K, wbits, wfmt and rfmt; the sum of their N must not exceed the
+ * workspace's maxN.  Each y_m equals what decdec_gemv would produce for
+ * matrix m alone. */
+int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x_f16_dev, int32_t k,
+                      decdec_ws* ws, void* stream);
+
 /* ------------------------------------------------ offline, on the device */
 
 /* Uniform min/max group-128 quantiser on the GPU (offline preparation; the

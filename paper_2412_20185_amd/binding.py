@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
     "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
-    "decdec_pack_residual_int4", "decdec_select_topk", "decdec_gemv", "decdec_gemv_idx",
+    "decdec_pack_residual_int4", "decdec_select_topk", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
     "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
 )
 
@@ -41,6 +41,12 @@ class Desc(C.Structure):
 
     def __init__(self, K, N, wbits, wfmt=W_UNIFORM_G128, rfmt=R_FP16):
         super().__init__(int(K), int(N), int(wbits), int(wfmt), int(rfmt))
+
+
+class Linear(C.Structure):
+    """decdec_linear: one weight matrix with its residual and output (for decdec_gemv_multi)."""
+    _fields_ = [("desc", C.POINTER(Desc)), ("Wq", C.c_void_p), ("scales", C.c_void_p), ("zeros_or_lut", C.c_void_p),
+                ("R_pinned", C.c_void_p), ("R_scales", C.c_void_p), ("y", C.c_void_p)]
 
 
 _lib = None
@@ -81,6 +87,7 @@ def lib() -> C.CDLL:
     L.decdec_gemv.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     L.decdec_gemv_idx.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     L.decdec_quantize_uniform.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    L.decdec_gemv_multi.argtypes = [i32, C.POINTER(Linear), vp, i32, vp, vp]
     _lib = L
     return L
 
@@ -217,6 +224,25 @@ def decdec_gemv_idx(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales,
     _check(lib().decdec_gemv_idx(C.byref(desc), _ptr(x), _ptr(Wq), _ptr(scales), _ptr(zeros_or_lut), _ptr(R_pinned),
                                  _ptr(R_scales), k, _ptr(idx), _ptr(xsel), _ptr(y), ws.handle, _stream(stream)),
            "decdec_gemv_idx")
+
+
+def make_linears(items) -> "C.Array":
+    """items: iterable of (desc, Wq, scales, zeros_or_lut, R_pinned, R_scales, y) -> ctypes array of decdec_linear.
+    Build it once and reuse it: the array keeps the descriptors alive."""
+    items = list(items)
+    arr = (Linear * len(items))()
+    arr._keep = items
+    for i, (desc, Wq, scales, zl, R, Rs, y) in enumerate(items):
+        arr[i].desc = C.pointer(desc)
+        arr[i].Wq, arr[i].scales, arr[i].zeros_or_lut = _ptr(Wq), _ptr(scales), _ptr(zl)
+        arr[i].R_pinned, arr[i].R_scales, arr[i].y = _ptr(R), _ptr(Rs), _ptr(y)
+    return arr
+
+
+def decdec_gemv_multi(linears, x, k: int, ws: Workspace, stream=None):
+    """linears: array from make_linears() (matrices sharing x)."""
+    _check(lib().decdec_gemv_multi(len(linears), linears, _ptr(x), k, ws.handle, _stream(stream)),
+           "decdec_gemv_multi")
 
 
 def decdec_quantize_uniform(desc: Desc, W_f32, Wq_out, scales_out, zeros_out, R_out=None, stream=None):

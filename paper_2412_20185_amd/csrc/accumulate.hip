@@ -13,26 +13,43 @@
 namespace decdec {
 namespace {
 
-__global__ __launch_bounds__(256) void accumulate_kernel(const float* __restrict__ gpart, int gslices,
-                                                        const float* __restrict__ cpart, int cslices, int N,
-                                                        _Float16* __restrict__ y) {
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
+struct AccJobs {
+    _Float16* y[kMaxMulti];
+    int col0[kMaxMulti + 1];
+    int n;
+};
+
+__global__ __launch_bounds__(256) void accumulate_kernel(const AccJobs jobs, const float* __restrict__ gpart,
+                                                        int gslices, const float* __restrict__ cpart, int cslices,
+                                                        int Ntot) {
+    const int c = blockIdx.x * 256 + threadIdx.x;  // concatenated column
+    if (c >= Ntot) return;
     float ob = 0.f;
 #pragma unroll 8
-    for (int s = 0; s < gslices; ++s) ob += gpart[(size_t)s * N + n];
+    for (int s = 0; s < gslices; ++s) ob += gpart[(size_t)s * Ntot + c];
     float odec = 0.f;
 #pragma unroll 8
-    for (int r = 0; r < cslices; ++r) odec += cpart[(size_t)r * N + n];
-    y[n] = (_Float16)(ob + odec);
+    for (int r = 0; r < cslices; ++r) odec += cpart[(size_t)r * Ntot + c];
+    int m = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxMulti; ++i) m += (i < jobs.n && c >= jobs.col0[i]) ? 1 : 0;
+    jobs.y[m][c - jobs.col0[m]] = (_Float16)(ob + odec);
 }
 
 }  // namespace
 
-hipError_t launch_accumulate(const float* gpart, int gslices, const float* cpart, int cslices, int N, void* y,
-                             hipStream_t stream) {
-    accumulate_kernel<<<dim3((N + 255) / 256), dim3(256), 0, stream>>>(gpart, gslices, cpart, cslices, N,
-                                                                       static_cast<_Float16*>(y));
+hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* gpart, int gslices,
+                             const float* cpart, int cslices, hipStream_t stream) {
+    AccJobs jobs{};
+    jobs.n = sh.n;
+    for (int m = 0; m < sh.n; ++m) {
+        jobs.y[m] = static_cast<_Float16*>(y[m]);
+        jobs.col0[m] = sh.col0[m];
+    }
+    jobs.col0[sh.n] = sh.col0[sh.n];
+    const int Ntot = sh.col0[sh.n];
+    accumulate_kernel<<<dim3((Ntot + 255) / 256), dim3(256), 0, stream>>>(jobs, gpart, gslices, cpart, cslices,
+                                                                          Ntot);
     return hipGetLastError();
 }
 

@@ -62,7 +62,7 @@ struct decdec_ws {
     float* gpart;    // [kMaxGemvSlices][maxN]
     float* cpart;    // [kMaxFetchSlices][maxN]
     const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
-    int pinned_n;
+    int pinned_n, pinned_next;
     // optional kernel timing: per call events g0,g1 (caller's stream) and s0,f0,f1 (side stream)
     hipEvent_t* prof_ev;   // [prof_cap][5]
     uint8_t* prof_mask;    // [prof_cap] bit0: gemv timed, bit1: select timed, bit2: fetch timed
@@ -338,31 +338,59 @@ int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k, int32_t* idx
     return DECDEC_OK;
 }
 
-static int gemv_common(const decdec_desc* d, const void* x, const void* Wq, const void* scales,
-                       const void* zeros_or_lut, const void* R_pinned, const void* R_scales, int32_t k,
-                       const int32_t* idx_in, const void* xsel_in, bool have_idx, void* y, decdec_ws* ws,
-                       void* stream_v) {
-    const int rc = check_desc(d);
-    if (rc != DECDEC_OK) return rc;
-    if (ws == nullptr || x == nullptr || Wq == nullptr || zeros_or_lut == nullptr || y == nullptr)
-        return DECDEC_EINVAL;
-    if (d->wfmt == DECDEC_W_UNIFORM_G128 && scales == nullptr) return DECDEC_EINVAL;
-    if (d->K > ws->maxK || d->N > ws->maxN || k < 0 || k > d->K || k > ws->maxk) return DECDEC_EINVAL;
+static int check_pinned_cached(decdec_ws* ws, const void* R_pinned) {
+    for (int i = 0; i < ws->pinned_n; ++i)
+        if (ws->pinned_ok[i] == R_pinned) return DECDEC_OK;
+    const int prc = decdec_check_pinned(R_pinned);
+    if (prc != DECDEC_OK) return prc;
+    ws->pinned_ok[ws->pinned_next] = R_pinned;
+    ws->pinned_next = (ws->pinned_next + 1) % kPinnedCache;
+    if (ws->pinned_n < kPinnedCache) ++ws->pinned_n;
+    return DECDEC_OK;
+}
+
+// count linears that share x (and therefore K, the selection, and one launch
+// of each kernel).  idx_in/xsel_in: caller-supplied selection or null.
+static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t k, const int32_t* idx_in,
+                       const void* xsel_in, bool have_idx, decdec_ws* ws, void* stream_v) {
+    if (lin == nullptr || count < 1 || count > kMaxMulti || ws == nullptr || x == nullptr) return DECDEC_EINVAL;
+    MultiShape sh{};
+    GemvOperands gop{};
+    FetchOperands fop{};
+    void* ys[kMaxMulti] = {};
+    sh.n = count;
+    const decdec_desc* d0 = lin[0].desc;
+    for (int m = 0; m < count; ++m) {
+        const decdec_linear& L = lin[m];
+        const int rc = check_desc(L.desc);
+        if (rc != DECDEC_OK) return rc;
+        if (L.desc->K != d0->K) return DECDEC_EINVAL;
+        if (L.desc->wbits != d0->wbits || L.desc->wfmt != d0->wfmt || L.desc->rfmt != d0->rfmt)
+            return DECDEC_EUNSUPPORTED;
+        if (L.Wq_dev == nullptr || L.zeros_or_lut_f16_dev == nullptr || L.y_f16_dev == nullptr) return DECDEC_EINVAL;
+        if (L.desc->wfmt == DECDEC_W_UNIFORM_G128 && L.scales_f16_dev == nullptr) return DECDEC_EINVAL;
+        sh.N[m] = L.desc->N;
+        sh.col0[m + 1] = sh.col0[m] + L.desc->N;
+        gop.Wq[m] = L.Wq_dev;
+        gop.scales[m] = L.scales_f16_dev;
+        gop.zeros_or_lut[m] = L.zeros_or_lut_f16_dev;
+        fop.R[m] = L.R_pinned;
+        fop.R_scales[m] = L.R_scales_f16_dev;
+        ys[m] = L.y_f16_dev;
+    }
+    sh.K = d0->K;
+    if (sh.K > ws->maxK || sh.col0[count] > ws->maxN || k < 0 || k > sh.K || k > ws->maxk) return DECDEC_EINVAL;
     if (k > 0) {
-        if (R_pinned == nullptr) return DECDEC_EINVAL;
-        if (d->rfmt == DECDEC_R_INT4_SYM_COL && R_scales == nullptr) return DECDEC_EINVAL;
         if (have_idx && (idx_in == nullptr || xsel_in == nullptr)) return DECDEC_EINVAL;
-        bool known = false;
-        for (int i = 0; i < ws->pinned_n; ++i) known = known || ws->pinned_ok[i] == R_pinned;
-        if (!known) {
-            const int prc = decdec_check_pinned(R_pinned);
+        for (int m = 0; m < count; ++m) {
+            if (lin[m].R_pinned == nullptr) return DECDEC_EINVAL;
+            if (d0->rfmt == DECDEC_R_INT4_SYM_COL && lin[m].R_scales_f16_dev == nullptr) return DECDEC_EINVAL;
+            const int prc = check_pinned_cached(ws, lin[m].R_pinned);
             if (prc != DECDEC_OK) return prc;
-            ws->pinned_ok[ws->pinned_n % kPinnedCache] = R_pinned;
-            if (ws->pinned_n < kPinnedCache) ++ws->pinned_n;
         }
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    const int kind = pack_kind(d);
+    const int kind = pack_kind(d0);
     hipEvent_t* pev = nullptr;
     uint8_t* pmask = nullptr;
     if (ws->prof_ev != nullptr && ws->prof_used < ws->prof_cap) {
@@ -380,14 +408,14 @@ static int gemv_common(const decdec_desc* d, const void* x, const void* Wq, cons
         const void* xsel = xsel_in;
         if (!have_idx) {
             if (pev) DD_HIP(hipEventRecord(pev[2], ws->side));
-            DD_HIP(launch_select_topk(x, d->K, k, ws->idx, ws->xsel, ws->side));
+            DD_HIP(launch_select_topk(x, sh.K, k, ws->idx, ws->xsel, ws->side));
             idx = ws->idx;
             xsel = ws->xsel;
             if (pev) *pmask |= 2;
         }
         if (pev) DD_HIP(hipEventRecord(pev[3], ws->side));
-        cslices = fetch_slices(d->rfmt, d->N, k, ws->fetch_split);
-        DD_HIP(launch_fetch(d->rfmt, R_pinned, R_scales, idx, xsel, k, d->K, d->N, ws->cpart, cslices, ws->side));
+        cslices = fetch_slices(d0->rfmt, sh, k, ws->fetch_split);
+        DD_HIP(launch_fetch(d0->rfmt, sh, fop, idx, xsel, k, ws->cpart, cslices, ws->side));
         if (pev) {
             DD_HIP(hipEventRecord(pev[4], ws->side));
             *pmask |= 4;
@@ -396,28 +424,50 @@ static int gemv_common(const decdec_desc* d, const void* x, const void* Wq, cons
     }
     int gslices = 0;
     if (pev) DD_HIP(hipEventRecord(pev[0], stream));
-    DD_HIP(launch_gemv(kind, Wq, scales, zeros_or_lut, x, ws->gpart, d->K, d->N, ws->gemv_gpw, &gslices, stream));
+    DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, ws->gemv_gpw, &gslices, stream));
     if (pev) {
         DD_HIP(hipEventRecord(pev[1], stream));
         *pmask |= 1;
     }
     if (k > 0) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
-    DD_HIP(launch_accumulate(ws->gpart, gslices, ws->cpart, cslices, d->N, y, stream));
+    DD_HIP(launch_accumulate(sh, ys, ws->gpart, gslices, ws->cpart, cslices, stream));
     return DECDEC_OK;
+}
+
+static decdec_linear one_linear(const decdec_desc* d, const void* Wq, const void* scales, const void* zl,
+                                const void* R, const void* Rs, void* y) {
+    decdec_linear L;
+    L.desc = d;
+    L.Wq_dev = Wq;
+    L.scales_f16_dev = scales;
+    L.zeros_or_lut_f16_dev = zl;
+    L.R_pinned = R;
+    L.R_scales_f16_dev = Rs;
+    L.y_f16_dev = y;
+    return L;
 }
 
 int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
                 const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev, int32_t k,
                 void* y_f16_dev, decdec_ws* ws, void* stream) {
-    return gemv_common(d, x_f16_dev, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, k,
-                       nullptr, nullptr, false, y_f16_dev, ws, stream);
+    if (d == nullptr) return DECDEC_EINVAL;
+    const decdec_linear L =
+        one_linear(d, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, y_f16_dev);
+    return gemv_common(1, &L, x_f16_dev, k, nullptr, nullptr, false, ws, stream);
 }
 
 int decdec_gemv_idx(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
                     const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev, int32_t k,
                     const int32_t* idx_dev, const void* xsel_f16_dev, void* y_f16_dev, decdec_ws* ws, void* stream) {
-    return gemv_common(d, x_f16_dev, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, k,
-                       idx_dev, xsel_f16_dev, true, y_f16_dev, ws, stream);
+    if (d == nullptr) return DECDEC_EINVAL;
+    const decdec_linear L =
+        one_linear(d, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, y_f16_dev);
+    return gemv_common(1, &L, x_f16_dev, k, idx_dev, xsel_f16_dev, true, ws, stream);
+}
+
+int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x_f16_dev, int32_t k, decdec_ws* ws,
+                      void* stream) {
+    return gemv_common(count, linears, x_f16_dev, k, nullptr, nullptr, false, ws, stream);
 }
 
 int decdec_quantize_uniform(const decdec_desc* d, const void* W_f32_dev, void* Wq_out_dev, void* scales_f16_out_dev,

@@ -25,20 +25,50 @@ __device__ __forceinline__ float h2f(uint32_t bits16) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
 }
 
-// Wave task (wc, rs): columns [wc*512, wc*512+512) of the rows j in slice rs.
-__global__ __launch_bounds__(256) void fetch_fp16_kernel(const uint4* __restrict__ R,
-                                                        const int32_t* __restrict__ idx,
-                                                        const uint16_t* __restrict__ xsel, int k, int K, int N,
-                                                        float* __restrict__ cpart, int wavecols, int slices) {
-    const int lane = threadIdx.x & 63;
+struct FetchJobs {
+    const uint4* R[kMaxMulti];
+    const uint16_t* Rs[kMaxMulti];
+    int N[kMaxMulti];
+    int col0[kMaxMulti];
+    int wc_end[kMaxMulti];  // cumulative count of wave-wide column segments up to and including matrix m
+    int n;
+};
+
+struct WaveTask {
+    int m, wc, rs;
+    bool valid;
+};
+
+// Task t of the grid: row slice rs = t / wavecols, column segment t % wavecols
+// of the concatenated matrices.
+__device__ __forceinline__ WaveTask wave_task(const FetchJobs& jobs, int wavecols, int slices) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int task = blockIdx.x * 4 + wave;
-    if (task >= wavecols * slices) return;
-    const int rs = task / wavecols, wc = task - rs * wavecols;
-    const int oct = wc * 64 + lane;  // 8 columns = one 16-byte piece of a row
+    WaveTask t;
+    t.valid = task < wavecols * slices;
+    t.rs = task / wavecols;
+    const int c = task - t.rs * wavecols;
+    int m = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxMulti - 1; ++i) m += (i + 1 < jobs.n && c >= jobs.wc_end[i]) ? 1 : 0;
+    t.m = m;
+    t.wc = c - (m > 0 ? jobs.wc_end[m - 1] : 0);
+    return t;
+}
+
+// Wave task (m, wc, rs): columns [wc*512, wc*512+512) of matrix m for the rows j in slice rs.
+__global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, const int32_t* __restrict__ idx,
+                                                        const uint16_t* __restrict__ xsel, int k, int K, int Ntot,
+                                                        float* __restrict__ cpart, int wavecols, int slices) {
+    const int lane = threadIdx.x & 63;
+    const WaveTask t = wave_task(jobs, wavecols, slices);
+    if (!t.valid) return;
+    const int N = jobs.N[t.m];
+    const uint4* __restrict__ R = jobs.R[t.m];
+    const int oct = t.wc * 64 + lane;  // 8 columns = one 16-byte piece of a row
     const bool active = oct * 8 < N;
     const int rows_per = (k + slices - 1) / slices;
-    const int j0 = rs * rows_per, j1 = min(j0 + rows_per, k);
+    const int j0 = t.rs * rows_per, j1 = min(j0 + rows_per, k);
     const size_t row16 = (size_t)(N / 8);
 
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -68,7 +98,7 @@ __global__ __launch_bounds__(256) void fetch_fp16_kernel(const uint4* __restrict
         }
     }
     if (active) {
-        float4* out = reinterpret_cast<float4*>(cpart + (size_t)rs * N + (size_t)oct * 8);
+        float4* out = reinterpret_cast<float4*>(cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)oct * 8);
         out[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
         out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
     }
@@ -76,20 +106,19 @@ __global__ __launch_bounds__(256) void fetch_fp16_kernel(const uint4* __restrict
 
 // 4-bit residuals (Section 4.2): a 16-byte piece holds 32 columns; a wave
 // covers 2048 columns.  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
-__global__ __launch_bounds__(256) void fetch_int4_kernel(const uint4* __restrict__ R,
-                                                        const uint16_t* __restrict__ Rs,
-                                                        const int32_t* __restrict__ idx,
-                                                        const uint16_t* __restrict__ xsel, int k, int K, int N,
+__global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, const int32_t* __restrict__ idx,
+                                                        const uint16_t* __restrict__ xsel, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int task = blockIdx.x * 4 + wave;
-    if (task >= wavecols * slices) return;
-    const int rs = task / wavecols, wc = task - rs * wavecols;
-    const int piece = wc * 64 + lane;  // 32 columns
+    const WaveTask t = wave_task(jobs, wavecols, slices);
+    if (!t.valid) return;
+    const int N = jobs.N[t.m];
+    const uint4* __restrict__ R = jobs.R[t.m];
+    const uint16_t* __restrict__ Rs = jobs.Rs[t.m];
+    const int piece = t.wc * 64 + lane;  // 32 columns
     const bool active = piece * 32 < N;
     const int rows_per = (k + slices - 1) / slices;
-    const int j0 = rs * rows_per, j1 = min(j0 + rows_per, k);
+    const int j0 = t.rs * rows_per, j1 = min(j0 + rows_per, k);
     const size_t row16 = (size_t)(N / 32);
 
     float acc[32];
@@ -125,7 +154,7 @@ __global__ __launch_bounds__(256) void fetch_int4_kernel(const uint4* __restrict
     }
     if (active) {
         const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * 32);
-        float4* out = reinterpret_cast<float4*>(cpart + (size_t)rs * N + (size_t)piece * 32);
+        float4* out = reinterpret_cast<float4*>(cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * 32);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const uint4 sv = s4[b];
@@ -144,10 +173,16 @@ __global__ __launch_bounds__(256) void fetch_int4_kernel(const uint4* __restrict
 
 inline int cols_per_wave(int rfmt) { return rfmt == 0 ? 512 : 2048; }
 
+inline int total_wavecols(int rfmt, const MultiShape& sh) {
+    int wc = 0;
+    for (int m = 0; m < sh.n; ++m) wc += (sh.N[m] + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
+    return wc;
+}
+
 }  // namespace
 
-int fetch_slices(int rfmt, int N, int k, int row_split) {
-    const int wavecols = (N + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
+int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split) {
+    const int wavecols = total_wavecols(rfmt, sh);
     int slices;
     if (row_split > 0) {
         slices = row_split;
@@ -161,20 +196,27 @@ int fetch_slices(int rfmt, int N, int k, int row_split) {
     return slices;
 }
 
-hipError_t launch_fetch(int rfmt, const void* R_pinned, const void* R_scales, const int32_t* idx, const void* xsel,
-                        int k, int K, int N, float* cpart, int slices, hipStream_t stream) {
-    const int wavecols = (N + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
-    const int tasks = wavecols * slices;
+hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const int32_t* idx,
+                        const void* xsel, int k, float* cpart, int slices, hipStream_t stream) {
+    FetchJobs jobs{};
+    jobs.n = sh.n;
+    int wc = 0;
+    for (int m = 0; m < sh.n; ++m) {
+        jobs.R[m] = static_cast<const uint4*>(op.R[m]);
+        jobs.Rs[m] = static_cast<const uint16_t*>(op.R_scales[m]);
+        jobs.N[m] = sh.N[m];
+        jobs.col0[m] = sh.col0[m];
+        wc += (sh.N[m] + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
+        jobs.wc_end[m] = wc;
+    }
+    const int tasks = wc * slices;
     const dim3 grid((unsigned)((tasks + 3) / 4)), block(256);
+    const uint16_t* xs = static_cast<const uint16_t*>(xsel);
+    const int Ntot = sh.col0[sh.n];
     if (rfmt == 0) {
-        fetch_fp16_kernel<<<grid, block, 0, stream>>>(static_cast<const uint4*>(R_pinned), idx,
-                                                      static_cast<const uint16_t*>(xsel), k, K, N, cpart, wavecols,
-                                                      slices);
+        fetch_fp16_kernel<<<grid, block, 0, stream>>>(jobs, idx, xs, k, sh.K, Ntot, cpart, wc, slices);
     } else {
-        fetch_int4_kernel<<<grid, block, 0, stream>>>(static_cast<const uint4*>(R_pinned),
-                                                      static_cast<const uint16_t*>(R_scales), idx,
-                                                      static_cast<const uint16_t*>(xsel), k, K, N, cpart, wavecols,
-                                                      slices);
+        fetch_int4_kernel<<<grid, block, 0, stream>>>(jobs, idx, xs, k, sh.K, Ntot, cpart, wc, slices);
     }
     return hipGetLastError();
 }

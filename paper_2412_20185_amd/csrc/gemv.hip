@@ -201,25 +201,41 @@ __device__ __forceinline__ float tile_dot(const TileRegs<KIND>& r, const LutTabl
     }
 }
 
-// grid: (N/64) * slices workgroups of 256 threads; workgroup (nt, ks) covers
-// column tile nt and groups [ks*4*gpw, (ks+1)*4*gpw), wave w of it the gpw
-// groups starting at (ks*4 + w)*gpw.  part is fp32 [slices][N].  The loads of
-// the next tile are issued before the current one is consumed.
+struct GemvJobs {
+    const uint4* Wq[kMaxMulti];
+    const uint16_t* scales[kMaxMulti];
+    const uint16_t* zeros_or_lut[kMaxMulti];
+    int N[kMaxMulti];
+    int col0[kMaxMulti];
+    int tile_end[kMaxMulti];  // cumulative count of 64-column tiles up to and including matrix m
+    int n;
+};
+
+// grid: (total tiles) * slices workgroups of 256 threads; workgroup (nt, ks)
+// covers column tile nt (of whichever matrix it falls in) and groups
+// [ks*4*gpw, (ks+1)*4*gpw), wave w of it the gpw groups starting at
+// (ks*4 + w)*gpw.  part is fp32 [slices][Ntot].  The loads of the next tile
+// are issued before the current one is consumed.
 template <int KIND>
-__global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
-                                                  const uint16_t* __restrict__ scales,
-                                                  const uint16_t* __restrict__ zeros_or_lut,
-                                                  const uint32_t* __restrict__ x32, float* __restrict__ part,
-                                                  int N, int G, int slices, int gpw) {
+__global__ __launch_bounds__(256) void gemv_kernel(const GemvJobs jobs, const uint32_t* __restrict__ x32,
+                                                  float* __restrict__ part, int Ntot, int G, int slices,
+                                                  int gpw) {
     constexpr int P = words_per_lane(KIND) / 4;  // 16-byte pieces per lane per tile
     constexpr int kTileStride = P * kTileCols;   // uint4 per tile
     __shared__ float red[kWavesPerBlock][kTileCols];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nt = blockIdx.x / slices;
-    const int ks = blockIdx.x - nt * slices;
+    const int gt = blockIdx.x / slices;  // tile index over all matrices
+    const int ks = blockIdx.x - gt * slices;
+    int m = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxMulti - 1; ++i) m += (i + 1 < jobs.n && gt >= jobs.tile_end[i]) ? 1 : 0;
+    const int nt = gt - (m > 0 ? jobs.tile_end[m - 1] : 0);
+    const int N = jobs.N[m];
     const int n = nt * kTileCols + lane;
+    const uint16_t* __restrict__ scales = jobs.scales[m];
+    const uint16_t* __restrict__ zeros_or_lut = jobs.zeros_or_lut[m];
 
     int g = (ks * kWavesPerBlock + wave) * gpw;
     const int g_end = min(g + gpw, G);
@@ -230,7 +246,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
     }
 
     float total = 0.f;
-    const uint4* tile = Wq + ((size_t)nt * G + g) * kTileStride + lane;
+    const uint4* tile = jobs.Wq[m] + ((size_t)nt * G + g) * kTileStride + lane;
     TileRegs<KIND> ra, rb;
     if (g < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g, N, n, lane);
     while (g < g_end) {
@@ -249,18 +265,17 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint4* __restrict__ Wq,
         float v = red[0][lane];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) v += red[w][lane];
-        part[(size_t)ks * N + n] = v;
+        part[(size_t)ks * Ntot + jobs.col0[m] + n] = v;
     }
 }
 
 }  // namespace
 
-int gemv_slices(int N, int G, int gpw_request, int* gpw_out) {
+int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out) {
     // One group per wavefront while that keeps the grid within what the chip
     // holds at once (256 CUs x 32 waves): the whole matrix is then requested in
     // one go.  Larger problems give every wavefront several groups.
-    const int tiles = N / kTileCols;
-    const long units = (long)tiles * G;
+    const long units = tiles * G;
     int gpw = gpw_request > 0 ? gpw_request : (int)((units + 8191) / 8192);
     if (gpw < 1) gpw = 1;
     int per_block = gpw * kWavesPerBlock;
@@ -274,26 +289,36 @@ int gemv_slices(int N, int G, int gpw_request, int* gpw_out) {
     return slices;
 }
 
-hipError_t launch_gemv(int kind, const void* Wq, const void* scales, const void* zeros_or_lut, const void* x,
-                       float* part, int K, int N, int gpw_request, int* slices_out, hipStream_t stream) {
-    const int G = K / kGroup;
+hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
+                       int gpw_request, int* slices_out, hipStream_t stream) {
+    const int G = sh.K / kGroup;
+    GemvJobs jobs{};
+    jobs.n = sh.n;
+    int tiles = 0;
+    for (int m = 0; m < sh.n; ++m) {
+        jobs.Wq[m] = static_cast<const uint4*>(op.Wq[m]);
+        jobs.scales[m] = static_cast<const uint16_t*>(op.scales[m]);
+        jobs.zeros_or_lut[m] = static_cast<const uint16_t*>(op.zeros_or_lut[m]);
+        jobs.N[m] = sh.N[m];
+        jobs.col0[m] = sh.col0[m];
+        tiles += sh.N[m] / kTileCols;
+        jobs.tile_end[m] = tiles;
+    }
     int gpw = 1;
-    const int slices = gemv_slices(N, G, gpw_request, &gpw);
+    const int slices = gemv_slices(tiles, G, gpw_request, &gpw);
     *slices_out = slices;
-    const dim3 grid((unsigned)((N / kTileCols) * slices)), block(256);
-    const uint4* w = static_cast<const uint4*>(Wq);
-    const uint16_t* s = static_cast<const uint16_t*>(scales);
-    const uint16_t* z = static_cast<const uint16_t*>(zeros_or_lut);
+    const dim3 grid((unsigned)(tiles * slices)), block(256);
     const uint32_t* x32 = static_cast<const uint32_t*>(x);
+    const int Ntot = sh.col0[sh.n];
     switch (kind) {
         case PACK_U4:
-            gemv_kernel<PACK_U4><<<grid, block, 0, stream>>>(w, s, z, x32, part, N, G, slices, gpw);
+            gemv_kernel<PACK_U4><<<grid, block, 0, stream>>>(jobs, x32, part, Ntot, G, slices, gpw);
             break;
         case PACK_U3:
-            gemv_kernel<PACK_U3><<<grid, block, 0, stream>>>(w, s, z, x32, part, N, G, slices, gpw);
+            gemv_kernel<PACK_U3><<<grid, block, 0, stream>>>(jobs, x32, part, Ntot, G, slices, gpw);
             break;
         case PACK_LUT3:
-            gemv_kernel<PACK_LUT3><<<grid, block, 0, stream>>>(w, s, z, x32, part, N, G, slices, gpw);
+            gemv_kernel<PACK_LUT3><<<grid, block, 0, stream>>>(jobs, x32, part, Ntot, G, slices, gpw);
             break;
         default:
             return hipErrorInvalidValue;

@@ -13,25 +13,48 @@ constexpr int kMaxFetchSlices = 64;  // fp32 partial rows the residual kernel ma
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectMaxK = 65536;
 
+// One call handles up to kMaxMulti weight matrices that share the activation
+// vector x (q/k/v, gate/up): their columns are treated as one concatenated
+// output of Ntot = sum N_m columns; matrix m owns columns [col0[m], col0[m]+N[m]).
+constexpr int kMaxMulti = 4;
+
+struct MultiShape {
+    int n;                    // matrices in this call
+    int K;                    // shared input channels
+    int N[kMaxMulti];         // output columns per matrix
+    int col0[kMaxMulti + 1];  // first concatenated column of matrix m; col0[n] = Ntot
+};
+
+struct GemvOperands {
+    const void* Wq[kMaxMulti];
+    const void* scales[kMaxMulti];
+    const void* zeros_or_lut[kMaxMulti];
+};
+
+struct FetchOperands {
+    const void* R[kMaxMulti];         // pinned residual rows
+    const void* R_scales[kMaxMulti];  // fp16 [N_m] (int4 residuals) or null
+};
+
 // gemv.hip ---------------------------------------------------------------
-// part: fp32 [slices][N]; *slices_out receives the number of rows written.
-hipError_t launch_gemv(int kind, const void* Wq, const void* scales, const void* zeros_or_lut, const void* x,
-                       float* part, int K, int N, int gpw_request, int* slices_out, hipStream_t stream);
-int gemv_slices(int N, int G, int gpw_request, int* gpw_out);
+// part: fp32 [slices][Ntot]; *slices_out receives the number of rows written.
+hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
+                       int gpw_request, int* slices_out, hipStream_t stream);
+int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out);
 
 // select.hip -------------------------------------------------------------
 hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream);
 
 // fetch.hip --------------------------------------------------------------
-// cpart: fp32 [slices][N]; row_split: requested slices (0 = automatic).
-int fetch_slices(int rfmt, int N, int k, int row_split);
-hipError_t launch_fetch(int rfmt, const void* R_pinned, const void* R_scales, const int32_t* idx, const void* xsel,
-                        int k, int K, int N, float* cpart, int slices, hipStream_t stream);
+// cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic).
+int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split);
+hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const int32_t* idx,
+                        const void* xsel, int k, float* cpart, int slices, hipStream_t stream);
 
 // accumulate.hip ---------------------------------------------------------
-// y[n] = fp16( sum_s gpart[s][n] + sum_r cpart[r][n] )
-hipError_t launch_accumulate(const float* gpart, int gslices, const float* cpart, int cslices, int N, void* y,
-                             hipStream_t stream);
+// y_m[n] = fp16( sum_s gpart[s][col0[m]+n] + sum_r cpart[r][col0[m]+n] )
+hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* gpart, int gslices,
+                             const float* cpart, int cslices, hipStream_t stream);
 
 // quantize.hip -----------------------------------------------------------
 hipError_t launch_quantize_uniform(int bits, const float* W, void* Wq, void* scales, void* zeros, void* R, int K,

@@ -50,3 +50,18 @@ class UniformLinear:
 
     def gemv(self, x: torch.Tensor, k: int, y: torch.Tensor, ws: B.Workspace, stream=None):
         B.decdec_gemv(self.desc, x, self.Wq, self.scales, self.zeros, self.R, None, k, y, ws, stream)
+
+
+class LinearGroup:
+    """Linear layers that consume the same activation vector (q/k/v, gate/up:
+    the fused layer types of Section 4.4): one selection, one launch per kernel
+    for the whole group through decdec_gemv_multi."""
+
+    def __init__(self, linears, ys):
+        self.linears = list(linears)
+        self.ys = list(ys)
+        self._arr = B.make_linears(
+            (l.desc, l.Wq, l.scales, l.zeros, l.R, None, y) for l, y in zip(self.linears, self.ys))
+
+    def gemv(self, x: torch.Tensor, k: int, ws: B.Workspace, stream=None):
+        B.decdec_gemv_multi(self._arr, x, k, ws, stream)

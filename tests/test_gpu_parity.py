@@ -141,3 +141,50 @@ def test_repeated_calls_are_bitwise_reproducible(ws):
             big.run(xb, 300, ws)
         y, _, _ = p.run(x, 81, ws)
         assert np.array_equal(y.view(np.uint16), first.view(np.uint16))
+
+
+@pytest.mark.parametrize("wfmt,bits,rfmt", [("uniform", 3, "fp16"), ("uniform", 4, "int4"), ("lut", 3, "fp16")])
+def test_multi_shared_x_matches_oracle_per_matrix(ws, wfmt, bits, rfmt):
+    """q/k/v style: three matrices share x, one selection and one launch per kernel."""
+    K = 2048
+    Ns = [1024, 192, 576]
+    probs = [Problem(workloads.weights(80, 0, i, K, N), bits, wfmt=wfmt, rfmt=rfmt, lut_iters=2,
+                     alphas=oracle.quantize.DEFAULT_ALPHAS[::10]) for i, N in enumerate(Ns)]
+    ys = [torch.full((N,), float("nan"), dtype=torch.float16, device="cuda") for N in Ns]
+    items = []
+    for p, y in zip(probs, ys):
+        d = p.device()
+        items.append((p.desc, d["Wq"], d["scales"], d["zl"], d["R"], d["Rs"], y))
+    lin = dd.make_linears(items)
+    for step, k in enumerate([0, 1, 40, K]):
+        x = workloads.x_gauss_outliers(80, 0, 0, step, K)
+        for y in ys:
+            y.fill_(float("nan"))
+        dd.decdec_gemv_multi(lin, torch.from_numpy(x).cuda(), k, ws)
+        torch.cuda.synchronize()
+        idx = ws.read_selection(k)[0] if k else np.zeros(0, np.int32)
+        for p, y in zip(probs, ys):
+            y_ref, sc = p.reference(x, k)
+            assert_parity(y.cpu().numpy(), y_ref, idx, sc, what=f"multi {wfmt}{bits}/{rfmt} N={p.N} k={k}")
+
+
+def test_multi_rejects_mismatched_matrices(ws):
+    a = Problem(workloads.weights(81, 0, 0, 256, 64), 4)
+    b = Problem(workloads.weights(81, 0, 1, 384, 64), 4)
+    c = Problem(workloads.weights(81, 0, 2, 256, 64), 3)
+    y = torch.empty(64, dtype=torch.float16, device="cuda")
+    x = torch.zeros(384, dtype=torch.float16, device="cuda")
+
+    def lin(*ps):
+        return dd.make_linears([(p.desc, p.device()["Wq"], p.device()["scales"], p.device()["zl"], p.device()["R"],
+                                 None, y) for p in ps])
+    with pytest.raises(dd.DecdecError) as e:
+        dd.decdec_gemv_multi(lin(a, b), x, 0, ws)          # different K
+    assert e.value.status == -1
+    with pytest.raises(dd.DecdecError) as e:
+        dd.decdec_gemv_multi(lin(a, c), x, 0, ws)          # different bit-width
+    assert e.value.status == -2
+    with pytest.raises(dd.DecdecError) as e:
+        dd.decdec_gemv_multi(lin(a, a, a, a, a), x, 0, ws)  # more than 4
+    assert e.value.status == -1
+    torch.cuda.synchronize()
