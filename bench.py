@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fetch-split", type=int, default=0)
     ap.add_argument("--graph", type=int, default=1, help="1: replay each distinct step as a captured HIP graph")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run a plain 256 MiB copy kernel (for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--grouping", choices=("grouped", "separate"), default="grouped",
                     help="grouped: q/k/v and gate/up (same x) go through one decdec_gemv_multi call each, "
                          "as the paper's four layer types; separate: seven decdec_gemv calls")
@@ -130,6 +132,15 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
+    if args.pmc_calibrate:
+        # a plain elementwise kernel that reads 256 MiB and writes 256 MiB, 4 times
+        a = torch.ones(64 << 20, dtype=torch.int32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(4):
+            torch.add(a, 1, out=b)
+        torch.cuda.synchronize()
+        del a, b
+
     # ------------------------------------------------------------ timed region
     for i in range(args.warmup):
         run_step(i, True)
@@ -206,6 +217,7 @@ def main() -> int:
             "avg_launch_us": round(f_ms * 1e3 / max(f_n, 1), 3),
         },
         "select_avg_us": round(s_ms * 1e3 / max(s_n, 1), 3),
+        "accumulate_avg_us": round(prof["accumulate"][0] * 1e3 / max(prof["accumulate"][1], 1), 3),
         "setup_s": round(setup_s, 1),
         "launch": "hip-graph replay" if args.graph else "eager",
         "grouping": args.grouping,

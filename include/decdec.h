@@ -105,23 +105,30 @@ int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, 
  * choice.  Affects later calls on this workspace. */
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
 
+/* How the partial results of the base GEMV and of the residual kernel are
+ * added.  on = 0 (default): by a small kernel of its own on the caller's
+ * stream.  on = 1: whichever of the two kernels completes a 64-column tile
+ * last adds it up (same bits, one launch fewer; slower on MI355X at the sizes
+ * measured, because the finalizing wave must read around the L2 caches). */
+int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on);
+
 /* Number of 128-channel groups each wavefront of the base GEMV walks through
  * (how finely K is split over the chip); 0 restores the built-in choice. */
 int decdec_ws_set_gemv_split(decdec_ws* ws, int32_t groups_per_wave);
 
 /* Kernel timing for benchmarks.  capacity > 0 allocates that many sets of HIP
  * events (set-up call: allocates, synchronises) and makes every later
- * decdec_gemv / decdec_gemv_idx on this workspace record events around its
- * base-GEMV kernel (on the caller's stream) and around its selection and
- * residual-fetch kernels (on the side stream); capacity == 0 turns it off and
- * frees the events.  Calls beyond `capacity` since the last read are not
- * timed. */
+ * decdec_gemv / _idx / _multi call on this workspace attach a (start, stop)
+ * event pair to each kernel it launches, which receive that dispatch's own
+ * begin and end timestamps (the duration a kernel trace reports);
+ * capacity == 0 turns it off and frees the events.  Calls beyond `capacity`
+ * since the last read are not timed.  Do not capture a graph while on. */
 int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity);
-/* Synchronous: waits for all recorded events, returns the summed elapsed
- * milliseconds per kernel class and the number of timed calls (calls[0]:
- * base GEMV, calls[1]: selection, calls[2]: fetch), then starts over.  Any
- * output pointer may be NULL. */
-int decdec_ws_read_profile(decdec_ws* ws, double* gemv_ms, double* select_ms, double* fetch_ms, int32_t* calls);
+/* Synchronous: waits for the device, then returns per kernel class the summed
+ * kernel durations in milliseconds (ms[4]) and the number of timed launches
+ * (calls[4]); class 0: base GEMV, 1: selection, 2: residual fetch + residual
+ * GEMV, 3: accumulate.  Starts over afterwards.  Either pointer may be NULL. */
+int decdec_ws_read_profile(decdec_ws* ws, double* ms, int32_t* calls);
 
 /* ------------------------------------------------- host helpers (offline) */
 

@@ -21,7 +21,7 @@ R_FP16, R_INT4_SYM_COL = 0, 1
 
 EXPORTED_SYMBOLS = (
     "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
-    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split",
+    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_select_topk", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
     "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
@@ -76,8 +76,8 @@ def lib() -> C.CDLL:
     L.decdec_ws_set_fetch_split.argtypes = [vp, i32]
     L.decdec_ws_set_profiling.argtypes = [vp, i32]
     L.decdec_ws_set_gemv_split.argtypes = [vp, i32]
-    L.decdec_ws_read_profile.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
-                                         C.POINTER(i32)]
+    L.decdec_ws_set_inkernel_accumulate.argtypes = [vp, i32]
+    L.decdec_ws_read_profile.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     L.decdec_packed_bytes.restype = sz
     L.decdec_packed_bytes.argtypes = [dp]
     L.decdec_pack_weights.argtypes = [dp, vp, vp]
@@ -139,6 +139,9 @@ class Workspace:
     def set_fetch_split(self, row_split: int):
         _check(lib().decdec_ws_set_fetch_split(self.handle, row_split), "decdec_ws_set_fetch_split")
 
+    def set_inkernel_accumulate(self, on: bool):
+        _check(lib().decdec_ws_set_inkernel_accumulate(self.handle, int(on)), "decdec_ws_set_inkernel_accumulate")
+
     def set_gemv_split(self, groups_per_wave: int):
         _check(lib().decdec_ws_set_gemv_split(self.handle, groups_per_wave), "decdec_ws_set_gemv_split")
 
@@ -146,12 +149,12 @@ class Workspace:
         _check(lib().decdec_ws_set_profiling(self.handle, capacity), "decdec_ws_set_profiling")
 
     def read_profile(self):
-        """Synchronous: {'gemv': (ms_total, calls), 'select': ..., 'fetch': ...} since the last read."""
-        g, s_, f = C.c_double(), C.c_double(), C.c_double()
-        n = (C.c_int32 * 3)()
-        _check(lib().decdec_ws_read_profile(self.handle, C.byref(g), C.byref(s_), C.byref(f), n),
-               "decdec_ws_read_profile")
-        return {"gemv": (g.value, n[0]), "select": (s_.value, n[1]), "fetch": (f.value, n[2])}
+        """Synchronous: {'gemv': (ms_total, launches), 'select': ..., 'fetch': ..., 'accumulate': ...}
+        kernel durations since the last read."""
+        ms = (C.c_double * 4)()
+        n = (C.c_int32 * 4)()
+        _check(lib().decdec_ws_read_profile(self.handle, ms, n), "decdec_ws_read_profile")
+        return {name: (ms[i], n[i]) for i, name in enumerate(("gemv", "select", "fetch", "accumulate"))}
 
     def last_selection_ptrs(self):
         a, b = C.c_void_p(), C.c_void_p()

@@ -36,10 +36,20 @@ __global__ __launch_bounds__(256) void accumulate_kernel(const AccJobs jobs, con
     jobs.y[m][c - jobs.col0[m]] = (_Float16)(ob + odec);
 }
 
+__global__ __launch_bounds__(256) void clear_u32_kernel(unsigned* p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 }  // namespace
 
+hipError_t launch_clear_u32(unsigned* p, int n, hipStream_t stream) {
+    clear_u32_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(p, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* gpart, int gslices,
-                             const float* cpart, int cslices, hipStream_t stream) {
+                             const float* cpart, int cslices, hipStream_t stream, const KernelTimer* tm) {
     AccJobs jobs{};
     jobs.n = sh.n;
     for (int m = 0; m < sh.n; ++m) {
@@ -48,9 +58,8 @@ hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* 
     }
     jobs.col0[sh.n] = sh.col0[sh.n];
     const int Ntot = sh.col0[sh.n];
-    accumulate_kernel<<<dim3((Ntot + 255) / 256), dim3(256), 0, stream>>>(jobs, gpart, gslices, cpart, cslices,
-                                                                          Ntot);
-    return hipGetLastError();
+    return launch_kernel(tm, accumulate_kernel, dim3((Ntot + 255) / 256), dim3(256), 0, stream, jobs, gpart, gslices,
+                         cpart, cslices, Ntot);
 }
 
 }  // namespace decdec

@@ -7,6 +7,7 @@
 #include <new>
 
 #include "../../include/decdec.h"
+#include "finalize.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -48,6 +49,8 @@ int check_desc(const decdec_desc* d) {
 }
 
 constexpr int kPinnedCache = 16;
+constexpr int kProfClasses = 4;              // base GEMV, selection, fetch, accumulate
+constexpr int kProfEvents = 2 * kProfClasses;  // a (start, stop) pair each
 
 }  // namespace
 
@@ -61,11 +64,14 @@ struct decdec_ws {
     void* xsel;      // fp16 [maxk]
     float* gpart;    // [kMaxGemvSlices][maxN]
     float* cpart;    // [kMaxFetchSlices][maxN]
+    unsigned* counters;  // [maxN/64] per-tile arrival counters, zero between calls
+    int32_t inkernel_accumulate;  // 1: the last producer of a tile adds the partial rows (no accumulate kernel)
+    int32_t counters_dirty;       // a call failed half-way: clear the counters before the next one
     const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
     int pinned_n, pinned_next;
-    // optional kernel timing: per call events g0,g1 (caller's stream) and s0,f0,f1 (side stream)
-    hipEvent_t* prof_ev;   // [prof_cap][5]
-    uint8_t* prof_mask;    // [prof_cap] bit0: gemv timed, bit1: select timed, bit2: fetch timed
+    // optional kernel timing: per call one (start, stop) event pair per kernel class
+    hipEvent_t* prof_ev;   // [prof_cap][kProfEvents]: gemv, select, fetch, accumulate
+    uint8_t* prof_mask;    // [prof_cap] bit c: class c was launched and timed
     int32_t prof_cap, prof_used;
 };
 
@@ -117,6 +123,9 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
     if (e == hipSuccess) e = hipMalloc(&ws->xsel, kk * 2);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->gpart), (size_t)kMaxGemvSlices * maxN * 4);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->cpart), (size_t)kMaxFetchSlices * maxN * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->counters), ((size_t)maxN / 64 + 1) * 4);
+    if (e == hipSuccess) e = hipMemset(ws->counters, 0, ((size_t)maxN / 64 + 1) * 4);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         const int rc = e == hipErrorOutOfMemory ? DECDEC_ENOMEM : hip_fail(e);
         (void)hipGetLastError();
@@ -129,7 +138,7 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
 
 static void free_profiling(decdec_ws* ws) {
     if (ws->prof_ev) {
-        for (int i = 0; i < ws->prof_cap * 5; ++i)
+        for (int i = 0; i < ws->prof_cap * kProfEvents; ++i)
             if (ws->prof_ev[i]) (void)hipEventDestroy(ws->prof_ev[i]);
         delete[] ws->prof_ev;
         delete[] ws->prof_mask;
@@ -144,7 +153,7 @@ int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity) {
     DD_HIP(hipDeviceSynchronize());
     free_profiling(ws);
     if (capacity == 0) return DECDEC_OK;
-    ws->prof_ev = new (std::nothrow) hipEvent_t[(size_t)capacity * 5]();
+    ws->prof_ev = new (std::nothrow) hipEvent_t[(size_t)capacity * kProfEvents]();
     ws->prof_mask = new (std::nothrow) uint8_t[capacity]();
     if (ws->prof_ev == nullptr || ws->prof_mask == nullptr) {
         delete[] ws->prof_ev;
@@ -154,7 +163,7 @@ int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity) {
         return DECDEC_ENOMEM;
     }
     ws->prof_cap = capacity;
-    for (int i = 0; i < capacity * 5; ++i) {
+    for (int i = 0; i < capacity * kProfEvents; ++i) {
         const hipError_t e = hipEventCreate(&ws->prof_ev[i]);
         if (e != hipSuccess) {
             free_profiling(ws);
@@ -164,41 +173,29 @@ int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity) {
     return DECDEC_OK;
 }
 
-int decdec_ws_read_profile(decdec_ws* ws, double* gemv_ms, double* select_ms, double* fetch_ms, int32_t* calls) {
+int decdec_ws_read_profile(decdec_ws* ws, double* ms_out, int32_t* calls_out) {
     if (ws == nullptr) return DECDEC_EINVAL;
-    double t[3] = {0, 0, 0};
-    int32_t n[3] = {0, 0, 0};
+    double t[kProfClasses] = {0, 0, 0, 0};
+    int32_t n[kProfClasses] = {0, 0, 0, 0};
     if (ws->prof_ev) {
         DD_HIP(hipDeviceSynchronize());
         for (int i = 0; i < ws->prof_used; ++i) {
-            hipEvent_t* ev = ws->prof_ev + (size_t)i * 5;
-            float ms = 0.f;
-            if (ws->prof_mask[i] & 1) {
-                DD_HIP(hipEventElapsedTime(&ms, ev[0], ev[1]));
-                t[0] += ms;
-                ++n[0];
-            }
-            if (ws->prof_mask[i] & 2) {
-                DD_HIP(hipEventElapsedTime(&ms, ev[2], ev[3]));
-                t[1] += ms;
-                ++n[1];
-            }
-            if (ws->prof_mask[i] & 4) {
-                DD_HIP(hipEventElapsedTime(&ms, ev[3], ev[4]));
-                t[2] += ms;
-                ++n[2];
+            hipEvent_t* ev = ws->prof_ev + (size_t)i * kProfEvents;
+            for (int c = 0; c < kProfClasses; ++c) {
+                if (ws->prof_mask[i] & (1 << c)) {
+                    float ms = 0.f;
+                    DD_HIP(hipEventElapsedTime(&ms, ev[2 * c], ev[2 * c + 1]));
+                    t[c] += ms;
+                    ++n[c];
+                }
             }
             ws->prof_mask[i] = 0;
         }
         ws->prof_used = 0;
     }
-    if (gemv_ms) *gemv_ms = t[0];
-    if (select_ms) *select_ms = t[1];
-    if (fetch_ms) *fetch_ms = t[2];
-    if (calls) {
-        calls[0] = n[0];
-        calls[1] = n[1];
-        calls[2] = n[2];
+    for (int c = 0; c < kProfClasses; ++c) {
+        if (ms_out) ms_out[c] = t[c];
+        if (calls_out) calls_out[c] = n[c];
     }
     return DECDEC_OK;
 }
@@ -216,6 +213,7 @@ int decdec_ws_destroy(decdec_ws* ws) {
     if (ws->xsel) (void)hipFree(ws->xsel);
     if (ws->gpart) (void)hipFree(ws->gpart);
     if (ws->cpart) (void)hipFree(ws->cpart);
+    if (ws->counters) (void)hipFree(ws->counters);
     delete ws;
     return DECDEC_OK;
 }
@@ -224,6 +222,12 @@ int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const
     if (ws == nullptr) return DECDEC_EINVAL;
     if (idx_dev) *idx_dev = ws->idx;
     if (xsel_f16_dev) *xsel_f16_dev = ws->xsel;
+    return DECDEC_OK;
+}
+
+int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on) {
+    if (ws == nullptr || (on != 0 && on != 1)) return DECDEC_EINVAL;
+    ws->inkernel_accumulate = on;
     return DECDEC_OK;
 }
 
@@ -391,47 +395,74 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const int kind = pack_kind(d0);
-    hipEvent_t* pev = nullptr;
+    KernelTimer timers[kProfClasses];
+    const KernelTimer* tm[kProfClasses] = {nullptr, nullptr, nullptr, nullptr};
     uint8_t* pmask = nullptr;
     if (ws->prof_ev != nullptr && ws->prof_used < ws->prof_cap) {
-        pev = ws->prof_ev + (size_t)ws->prof_used * 5;
+        hipEvent_t* ev = ws->prof_ev + (size_t)ws->prof_used * kProfEvents;
+        for (int c = 0; c < kProfClasses; ++c) {
+            timers[c] = KernelTimer{ev[2 * c], ev[2 * c + 1]};
+            tm[c] = &timers[c];
+        }
         pmask = ws->prof_mask + ws->prof_used;
         ++ws->prof_used;
     }
 
-    int cslices = 0;
-    if (k > 0) {
-        // Section 4.1: all compensation steps run beside the base GEMV on another stream.
-        DD_HIP(hipEventRecord(ws->ev_fork, stream));
-        DD_HIP(hipStreamWaitEvent(ws->side, ws->ev_fork, 0));
-        const int32_t* idx = idx_in;
-        const void* xsel = xsel_in;
-        if (!have_idx) {
-            if (pev) DD_HIP(hipEventRecord(pev[2], ws->side));
-            DD_HIP(launch_select_topk(x, sh.K, k, ws->idx, ws->xsel, ws->side));
-            idx = ws->idx;
-            xsel = ws->xsel;
-            if (pev) *pmask |= 2;
-        }
-        if (pev) DD_HIP(hipEventRecord(pev[3], ws->side));
-        cslices = fetch_slices(d0->rfmt, sh, k, ws->fetch_split);
-        DD_HIP(launch_fetch(d0->rfmt, sh, fop, idx, xsel, k, ws->cpart, cslices, ws->side));
-        if (pev) {
-            DD_HIP(hipEventRecord(pev[4], ws->side));
-            *pmask |= 4;
-        }
-        DD_HIP(hipEventRecord(ws->ev_join, ws->side));
+    // Split of the work, known up front because each kernel must know how many
+    // partial rows the other one contributes.
+    long tiles = 0;
+    for (int m = 0; m < count; ++m) tiles += sh.N[m] / kTileCols;
+    int gpw = 1;
+    const int gslices = gemv_slices(tiles, sh.K / kGroup, ws->gemv_gpw, &gpw);
+    const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, ws->fetch_split) : 0;
+
+    FinalizeArgs fa{};
+    int t0 = 0;
+    for (int m = 0; m < count; ++m) {
+        fa.y[m] = static_cast<_Float16*>(ys[m]);
+        fa.col0[m] = sh.col0[m];
+        fa.tile0[m] = t0;
+        t0 += sh.N[m] / kTileCols;
     }
-    int gslices = 0;
-    if (pev) DD_HIP(hipEventRecord(pev[0], stream));
-    DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, ws->gemv_gpw, &gslices, stream));
-    if (pev) {
-        DD_HIP(hipEventRecord(pev[1], stream));
-        *pmask |= 1;
+    fa.gpart = ws->gpart;
+    fa.cpart = ws->cpart;
+    fa.gslices = gslices;
+    fa.cslices = cslices;
+    fa.Ntot = sh.col0[count];
+    fa.counters = ws->inkernel_accumulate ? ws->counters : nullptr;
+
+    if (ws->counters_dirty) {
+        DD_HIP(launch_clear_u32(ws->counters, ws->maxN / 64 + 1, stream));
+        ws->counters_dirty = 0;
     }
-    if (k > 0) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
-    DD_HIP(launch_accumulate(sh, ys, ws->gpart, gslices, ws->cpart, cslices, stream));
-    return DECDEC_OK;
+    const int rc_enq = [&]() -> int {
+        if (k > 0) {
+            // Section 4.1: all compensation steps run beside the base GEMV on another stream.
+            DD_HIP(hipEventRecord(ws->ev_fork, stream));
+            DD_HIP(hipStreamWaitEvent(ws->side, ws->ev_fork, 0));
+            const int32_t* idx = idx_in;
+            const void* xsel = xsel_in;
+            if (!have_idx) {
+                DD_HIP(launch_select_topk(x, sh.K, k, ws->idx, ws->xsel, ws->side, tm[1]));
+                idx = ws->idx;
+                xsel = ws->xsel;
+                if (pmask) *pmask |= 2;
+            }
+            DD_HIP(launch_fetch(d0->rfmt, sh, fop, idx, xsel, k, ws->cpart, cslices, fa, ws->side, tm[2]));
+            if (pmask) *pmask |= 4;
+            DD_HIP(hipEventRecord(ws->ev_join, ws->side));
+        }
+        DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, gslices, gpw, fa, stream, tm[0]));
+        if (pmask) *pmask |= 1;
+        if (k > 0) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
+        if (!ws->inkernel_accumulate) {
+            DD_HIP(launch_accumulate(sh, ys, ws->gpart, gslices, ws->cpart, cslices, stream, tm[3]));
+            if (pmask) *pmask |= 8;
+        }
+        return DECDEC_OK;
+    }();
+    if (rc_enq != DECDEC_OK) ws->counters_dirty = 1;  // some producers may never arrive
+    return rc_enq;
 }
 
 static decdec_linear one_linear(const decdec_desc* d, const void* Wq, const void* scales, const void* zl,

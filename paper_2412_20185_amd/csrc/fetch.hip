@@ -14,6 +14,7 @@
 // writes one fp32 partial row and the accumulate kernel adds them.
 #include <hip/hip_runtime.h>
 
+#include "finalize.h"
 #include "kernels.h"
 
 namespace decdec {
@@ -57,7 +58,8 @@ __device__ __forceinline__ WaveTask wave_task(const FetchJobs& jobs, int wavecol
 }
 
 // Wave task (m, wc, rs): columns [wc*512, wc*512+512) of matrix m for the rows j in slice rs.
-__global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, const int32_t* __restrict__ idx,
+__global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, const FinalizeArgs fa,
+                                                        const int32_t* __restrict__ idx,
                                                         const uint16_t* __restrict__ xsel, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
     const int lane = threadIdx.x & 63;
@@ -98,15 +100,22 @@ __global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, c
         }
     }
     if (active) {
-        float4* out = reinterpret_cast<float4*>(cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)oct * 8);
-        out[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)oct * 8;
+        if (fa.counters != nullptr) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) store_partial(out + i, acc[i], true);
+        } else {
+            reinterpret_cast<float4*>(out)[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            reinterpret_cast<float4*>(out)[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        }
     }
+    if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, t.m, t.wc * 8, min(8, N / 64 - t.wc * 8), lane);
 }
 
 // 4-bit residuals (Section 4.2): a 16-byte piece holds 32 columns; a wave
 // covers 2048 columns.  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
-__global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, const int32_t* __restrict__ idx,
+__global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, const FinalizeArgs fa,
+                                                        const int32_t* __restrict__ idx,
                                                         const uint16_t* __restrict__ xsel, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
     const int lane = threadIdx.x & 63;
@@ -154,7 +163,8 @@ __global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, c
     }
     if (active) {
         const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * 32);
-        float4* out = reinterpret_cast<float4*>(cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * 32);
+        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * 32;
+        const bool coherent = fa.counters != nullptr;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const uint4 sv = s4[b];
@@ -165,10 +175,11 @@ __global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, c
                 r[2 * c] = acc[8 * b + 2 * c] * h2f(sw[c] & 0xFFFFu);
                 r[2 * c + 1] = acc[8 * b + 2 * c + 1] * h2f(sw[c] >> 16);
             }
-            out[2 * b] = make_float4(r[0], r[1], r[2], r[3]);
-            out[2 * b + 1] = make_float4(r[4], r[5], r[6], r[7]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) store_partial(out + 8 * b + i, r[i], coherent);
         }
     }
+    if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, t.m, t.wc * 32, min(32, N / 64 - t.wc * 32), lane);
 }
 
 inline int cols_per_wave(int rfmt) { return rfmt == 0 ? 512 : 2048; }
@@ -197,7 +208,8 @@ int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split) {
 }
 
 hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const int32_t* idx,
-                        const void* xsel, int k, float* cpart, int slices, hipStream_t stream) {
+                        const void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
+                        hipStream_t stream, const KernelTimer* tm) {
     FetchJobs jobs{};
     jobs.n = sh.n;
     int wc = 0;
@@ -214,11 +226,11 @@ hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op,
     const uint16_t* xs = static_cast<const uint16_t*>(xsel);
     const int Ntot = sh.col0[sh.n];
     if (rfmt == 0) {
-        fetch_fp16_kernel<<<grid, block, 0, stream>>>(jobs, idx, xs, k, sh.K, Ntot, cpart, wc, slices);
-    } else {
-        fetch_int4_kernel<<<grid, block, 0, stream>>>(jobs, idx, xs, k, sh.K, Ntot, cpart, wc, slices);
+        return launch_kernel(tm, fetch_fp16_kernel, grid, block, 0, stream, jobs, fa, idx, xs, k, sh.K, Ntot, cpart,
+                             wc, slices);
     }
-    return hipGetLastError();
+    return launch_kernel(tm, fetch_int4_kernel, grid, block, 0, stream, jobs, fa, idx, xs, k, sh.K, Ntot, cpart, wc,
+                         slices);
 }
 
 }  // namespace decdec

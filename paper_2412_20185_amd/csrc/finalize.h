@@ -1,0 +1,87 @@
+// Step 4 of dynamic error compensation (DecDEC Section 4.1), o = o_b + o_dec,
+// folded into the kernels that produce the two terms.
+//
+// The base GEMV leaves `gslices` fp32 partial rows and the residual kernel
+// `cslices`; every 64-column tile of the output has a counter.  A producer
+// that has written its part of a tile increments the tile's counter; whichever
+// producer brings the counter to gslices + cslices adds all partial rows of
+// that tile in a fixed order, rounds once to fp16, writes y and resets the
+// counter.  Nobody waits for anybody, the sum does not depend on who came
+// last, and no extra launch is needed.  (The paper adds o_dec into o_b with
+// atomics from its fused kernel, Section 4.3; this keeps the "no extra kernel"
+// property without making the result depend on the order of floating-point
+// atomics.)
+//
+// Visibility across the eight L2 caches of the chip without flushing them: a
+// device-scope fence writes back and invalidates a whole L2, which costs more
+// than the kernels themselves when a thousand workgroups do it.  Instead the
+// partial rows are written with device-scope atomic stores (they write through
+// the L2), the wave waits until those stores have completed (s_waitcnt
+// vmcnt(0)) before it increments the counter with a device-scope atomic, and
+// the finalizing wave reads the partial rows with device-scope atomic loads
+// (they do not hit in a stale L2 line).  That is release/acquire on exactly
+// these locations.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace decdec {
+
+struct FinalizeArgs {
+    _Float16* y[kMaxMulti];
+    int col0[kMaxMulti];    // first concatenated column of matrix m
+    int tile0[kMaxMulti];   // first tile (64 columns) of matrix m among all tiles
+    const float* gpart;     // [gslices][Ntot]
+    const float* cpart;     // [cslices][Ntot]
+    unsigned* counters;     // one per tile, zero between calls; null: a separate kernel accumulates
+    int gslices, cslices, Ntot;
+};
+
+// Store of a partial result that other workgroups (possibly behind another L2) will read.
+__device__ __forceinline__ void store_partial(float* p, float v, bool coherent) {
+    if (coherent) {
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        *p = v;
+    }
+}
+
+__device__ __forceinline__ float load_partial(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// All 64 lanes: add the partial rows of tile nt of matrix m, write y, reset the counter.
+__device__ __forceinline__ void finalize_tile(const FinalizeArgs& fa, int m, int nt, int lane) {
+    const int cc = fa.col0[m] + nt * 64 + lane;
+    float ob = 0.f, odec = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < fa.gslices; ++s) ob += load_partial(fa.gpart + (size_t)s * fa.Ntot + cc);
+#pragma unroll 8
+    for (int r = 0; r < fa.cslices; ++r) odec += load_partial(fa.cpart + (size_t)r * fa.Ntot + cc);
+    fa.y[m][nt * 64 + lane] = (_Float16)(ob + odec);
+    if (lane == 0) fa.counters[fa.tile0[m] + nt] = 0;  // ready for the next call (stream-ordered after this one)
+}
+
+// Called by all 64 lanes of a wavefront after it has written (store_partial,
+// coherent) its partial row for tiles [nt0, nt0 + ntiles) of matrix m
+// (ntiles <= 64): counts the wave in on each of those tiles and finalizes the
+// tiles it completes.
+__device__ __forceinline__ void tiles_arrive_and_finalize(const FinalizeArgs& fa, int m, int nt0, int ntiles,
+                                                          int lane) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's partial rows have been performed
+    bool last = false;
+    if (lane < ntiles) {
+        const unsigned old = __hip_atomic_fetch_add(&fa.counters[fa.tile0[m] + nt0 + lane], 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+        last = old + 1 == (unsigned)(fa.gslices + fa.cslices);
+    }
+    unsigned long long mask = __ballot(last);
+    while (mask) {
+        const int j = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        finalize_tile(fa, m, nt0 + j, lane);
+    }
+}
+
+}  // namespace decdec

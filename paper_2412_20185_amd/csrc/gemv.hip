@@ -23,6 +23,7 @@
 //     the accumulate kernel (accumulate.hip) adds the partial rows.
 #include <hip/hip_runtime.h>
 
+#include "finalize.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -217,9 +218,9 @@ struct GemvJobs {
 // (ks*4 + w)*gpw.  part is fp32 [slices][Ntot].  The loads of the next tile
 // are issued before the current one is consumed.
 template <int KIND>
-__global__ __launch_bounds__(256) void gemv_kernel(const GemvJobs jobs, const uint32_t* __restrict__ x32,
-                                                  float* __restrict__ part, int Ntot, int G, int slices,
-                                                  int gpw) {
+__global__ __launch_bounds__(256) void gemv_kernel(const GemvJobs jobs, const FinalizeArgs fa,
+                                                  const uint32_t* __restrict__ x32, float* __restrict__ part,
+                                                  int Ntot, int G, int slices, int gpw) {
     constexpr int P = words_per_lane(KIND) / 4;  // 16-byte pieces per lane per tile
     constexpr int kTileStride = P * kTileCols;   // uint4 per tile
     __shared__ float red[kWavesPerBlock][kTileCols];
@@ -265,7 +266,8 @@ __global__ __launch_bounds__(256) void gemv_kernel(const GemvJobs jobs, const ui
         float v = red[0][lane];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) v += red[w][lane];
-        part[(size_t)ks * Ntot + jobs.col0[m] + n] = v;
+        store_partial(part + (size_t)ks * Ntot + jobs.col0[m] + n, v, fa.counters != nullptr);
+        if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, m, nt, 1, lane);
     }
 }
 
@@ -290,7 +292,7 @@ int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out) {
 }
 
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
-                       int gpw_request, int* slices_out, hipStream_t stream) {
+                       int slices, int gpw, const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm) {
     const int G = sh.K / kGroup;
     GemvJobs jobs{};
     jobs.n = sh.n;
@@ -304,26 +306,22 @@ hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, c
         tiles += sh.N[m] / kTileCols;
         jobs.tile_end[m] = tiles;
     }
-    int gpw = 1;
-    const int slices = gemv_slices(tiles, G, gpw_request, &gpw);
-    *slices_out = slices;
     const dim3 grid((unsigned)(tiles * slices)), block(256);
     const uint32_t* x32 = static_cast<const uint32_t*>(x);
     const int Ntot = sh.col0[sh.n];
     switch (kind) {
         case PACK_U4:
-            gemv_kernel<PACK_U4><<<grid, block, 0, stream>>>(jobs, x32, part, Ntot, G, slices, gpw);
-            break;
+            return launch_kernel(tm, gemv_kernel<PACK_U4>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G, slices,
+                                 gpw);
         case PACK_U3:
-            gemv_kernel<PACK_U3><<<grid, block, 0, stream>>>(jobs, x32, part, Ntot, G, slices, gpw);
-            break;
+            return launch_kernel(tm, gemv_kernel<PACK_U3>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G, slices,
+                                 gpw);
         case PACK_LUT3:
-            gemv_kernel<PACK_LUT3><<<grid, block, 0, stream>>>(jobs, x32, part, Ntot, G, slices, gpw);
-            break;
+            return launch_kernel(tm, gemv_kernel<PACK_LUT3>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G,
+                                 slices, gpw);
         default:
             return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace decdec

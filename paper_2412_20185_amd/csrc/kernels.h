@@ -2,6 +2,7 @@
 // translation units.  Every launcher validates nothing: api.hip has already
 // checked shapes against what the kernels and their grids assume.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -12,6 +13,24 @@ constexpr int kMaxGemvSlices = 64;   // fp32 partial rows the base GEMV may writ
 constexpr int kMaxFetchSlices = 64;  // fp32 partial rows the residual kernel may write
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectMaxK = 65536;
+
+// Optional pair of events that receive the begin and end timestamps of one
+// kernel dispatch (what a kernel trace reports as its duration).
+struct KernelTimer {
+    hipEvent_t start, stop;
+};
+
+// Launches `kernel`; with a timer the dispatch's own timestamps go to its events.
+template <typename F, typename... Args>
+inline hipError_t launch_kernel(const KernelTimer* tm, F kernel, dim3 grid, dim3 block, unsigned lds,
+                                hipStream_t stream, Args... args) {
+    if (tm != nullptr) {
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, tm->start, tm->stop, 0, args...);
+    } else {
+        kernel<<<grid, block, lds, stream>>>(args...);
+    }
+    return hipGetLastError();
+}
 
 // One call handles up to kMaxMulti weight matrices that share the activation
 // vector x (q/k/v, gate/up): their columns are treated as one concatenated
@@ -38,23 +57,30 @@ struct FetchOperands {
 
 // gemv.hip ---------------------------------------------------------------
 // part: fp32 [slices][Ntot]; *slices_out receives the number of rows written.
+struct FinalizeArgs;
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
-                       int gpw_request, int* slices_out, hipStream_t stream);
+                       int slices, int gpw, const FinalizeArgs& fa, hipStream_t stream,
+                       const KernelTimer* tm = nullptr);
 int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out);
 
 // select.hip -------------------------------------------------------------
-hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream);
+hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream,
+                              const KernelTimer* tm = nullptr);
 
 // fetch.hip --------------------------------------------------------------
 // cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic).
 int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split);
 hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const int32_t* idx,
-                        const void* xsel, int k, float* cpart, int slices, hipStream_t stream);
+                        const void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
+                        hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // accumulate.hip ---------------------------------------------------------
 // y_m[n] = fp16( sum_s gpart[s][col0[m]+n] + sum_r cpart[r][col0[m]+n] )
 hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* gpart, int gslices,
-                             const float* cpart, int cslices, hipStream_t stream);
+                             const float* cpart, int cslices, hipStream_t stream, const KernelTimer* tm = nullptr);
+
+// A fill kernel (not hipMemsetAsync, so that callers may capture the call in a graph).
+hipError_t launch_clear_u32(unsigned* p, int n, hipStream_t stream);
 
 // quantize.hip -----------------------------------------------------------
 hipError_t launch_quantize_uniform(int bits, const float* W, void* Wq, void* scales, void* zeros, void* R, int K,

@@ -23,7 +23,8 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const uint16_t* __
 
 }  // namespace
 
-hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream) {
+hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream,
+                              const KernelTimer* tm) {
     const size_t lds = (size_t)K * 2;
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_topk_kernel<1024>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSelectMaxK * 2);
@@ -31,11 +32,11 @@ hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, voi
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* xs = static_cast<uint16_t*>(xsel_out);
     if (K <= 8192) {
-        select_topk_kernel<256><<<dim3(1), dim3(256), lds, stream>>>(xp, K, k, idx_out, xs);
-    } else {
-        select_topk_kernel<1024><<<dim3(1), dim3(1024), lds, stream>>>(xp, K, k, idx_out, xs);
+        return launch_kernel(tm, select_topk_kernel<256>, dim3(1), dim3(256), (unsigned)lds, stream, xp, K, k, idx_out,
+                             xs);
     }
-    return hipGetLastError();
+    return launch_kernel(tm, select_topk_kernel<1024>, dim3(1), dim3(1024), (unsigned)lds, stream, xp, K, k, idx_out,
+                         xs);
 }
 
 }  // namespace decdec

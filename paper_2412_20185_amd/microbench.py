@@ -1,0 +1,198 @@
+"""Kernel-level measurements of the library on one MI355X.
+
+    python -m paper_2412_20185_amd.microbench gemv     base GEMV kernel per shape: us, GB/s, fraction of 8 TB/s
+    python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and row split: us, GB/s
+    python -m paper_2412_20185_amd.microbench ksweep   latency of a Llama-3-8B layer versus k (4-bit weights),
+                                                       next to the knee model of the paper (Section 5.1)
+
+Kernel durations are the dispatch timestamps the library records when
+profiling is switched on (decdec_ws_set_profiling), i.e. what a kernel trace
+reports.  Weights are random bytes in the packed layout (timing does not depend
+on their values); several copies are rotated so that they come from HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import sys
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+HBM_PEAK_GBS = 8000.0
+LINK_PEAK_GBS = 64.0
+
+SHAPES_8B = [("q/o", 4096, 4096), ("k/v", 4096, 1024), ("gate/up", 4096, 14336), ("down", 14336, 4096),
+             ("q+k+v", 4096, 6144), ("gate+up", 4096, 28672)]
+SHAPES_70B = [("q/o", 8192, 8192), ("k/v", 8192, 1024), ("gate/up", 8192, 28672), ("down", 28672, 8192)]
+
+
+def _operands(K, N, bits, wfmt, copies_bytes=600e6):
+    d = B.Desc(K, N, bits, wfmt)
+    nb = B.decdec_packed_bytes(d)
+    copies = max(2, int(copies_bytes // nb) + 1)
+    Wq = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda") for _ in range(copies)]
+    if wfmt == B.W_UNIFORM_G128:
+        sc = torch.full((K // 128, N), 0.01, dtype=torch.float16, device="cuda")
+        zl = torch.full((K // 128, N), 3.0, dtype=torch.float16, device="cuda")
+        bytes_ = K * N * bits // 8 + 4 * N * (K // 128) + 2 * K + 2 * N
+    else:
+        sc = None
+        zl = (torch.sort(torch.randn(N, 8, device="cuda"), dim=1).values * 0.02).half().contiguous()
+        bytes_ = K * N * bits // 8 + 16 * N + 2 * K + 2 * N
+    return d, Wq, sc, zl, bytes_
+
+
+def gemv(args):
+    ws = B.Workspace(28672, 28672, 16)
+    print(f"{'model':4s} {'shape':8s} {'K':>6s} {'N':>6s} {'fmt':5s} {'MB':>8s} {'kernel us':>10s} {'GB/s':>8s} {'of 8TB/s':>9s}")
+    for model, shapes in (("8B", SHAPES_8B), ("70B", SHAPES_70B)):
+        for name, K, N in shapes:
+            for bits, wfmt, tag in ((3, B.W_UNIFORM_G128, "u3"), (4, B.W_UNIFORM_G128, "u4"), (3, B.W_LUT_COL8, "lut3")):
+                d, Wq, sc, zl, nbytes = _operands(K, N, bits, wfmt)
+                x = torch.randn(K, device="cuda").half()
+                y = torch.empty(N, dtype=torch.float16, device="cuda")
+                for i in range(4):
+                    B.decdec_gemv(d, x, Wq[i % len(Wq)], sc, zl, None, None, 0, y, ws)
+                torch.cuda.synchronize()
+                ws.set_profiling(args.reps)
+                for i in range(args.reps):
+                    B.decdec_gemv(d, x, Wq[i % len(Wq)], sc, zl, None, None, 0, y, ws)
+                ms, n = ws.read_profile()["gemv"]
+                ws.set_profiling(0)
+                us = ms * 1e3 / n
+                gbs = nbytes / us / 1e3
+                print(f"{model:4s} {name:8s} {K:6d} {N:6d} {tag:5s} {nbytes / 1e6:8.2f} {us:10.2f} {gbs:8.0f} "
+                      f"{gbs / HBM_PEAK_GBS:9.3f}", flush=True)
+                del Wq
+    ws.close()
+
+
+def fetch(args):
+    ws = B.Workspace(28672, 28672, 4096)
+    cases = [(4096, 1024, 81), (4096, 4096, 81), (4096, 6144, 81), (4096, 14336, 81), (14336, 4096, 286),
+             (4096, 28672, 81), (4096, 4096, 512), (8192, 28672, 81), (28672, 8192, 286)]
+    print("residual fetch kernel (fp16 rows, zero-copy): us / GB/s per row split (0 = built-in choice)")
+    for K, N, k in cases:
+        d, Wq, sc, zl, _ = _operands(K, N, 3, B.W_UNIFORM_G128, copies_bytes=0)
+        R = torch.empty((K, N), dtype=torch.float16, pin_memory=True)
+        R.normal_(0, 0.003)
+        xs = [torch.randn(K, device="cuda").half() for _ in range(8)]
+        y = torch.empty(N, dtype=torch.float16, device="cuda")
+        line = f"K {K:5d} N {N:5d} k {k:4d} ({k * N * 2 / 1e6:5.2f} MB):"
+        for sp in (0, 2, 4, 8, 16, 32, 64):
+            ws.set_fetch_split(sp)
+            for i in range(3):
+                B.decdec_gemv(d, xs[i % 8], Wq[0], sc, zl, R, None, k, y, ws)
+            torch.cuda.synchronize()
+            ws.set_profiling(args.reps)
+            for i in range(args.reps):
+                B.decdec_gemv(d, xs[i % 8], Wq[0], sc, zl, R, None, k, y, ws)
+            ms, n = ws.read_profile()["fetch"]
+            ws.set_profiling(0)
+            us = ms * 1e3 / n
+            line += f"  s{sp}: {us:6.1f} / {k * N * 2 / us / 1e3:4.1f}"
+        print(line, flush=True)
+        del R
+    ws.set_fetch_split(0)
+    ws.close()
+
+
+def ksweep(args):
+    """Config-3 style: one Llama-3-8B-shaped layer, 4-bit weights, fp16 host
+    residuals, k_chunk channels per 1024 input channels; activations redrawn
+    each step.  Reports wall time per layer step (HIP-graph replay), per-kernel
+    averages, and the paper's model t(k) = max(t_base, k N r/8 / BW_link)."""
+    from .layer import LinearGroup, UniformLinear
+    import workloads
+    shapes = workloads.LLAMA3_8B_LAYER
+    layers = []
+    for l in range(args.layers):
+        layers.append({name: UniformLinear(workloads.weights(3, l, name, K, N), 4) for name, K, N, _ in shapes})
+    order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
+    ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
+    groups = [[LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for _, names in order] for lins in layers]
+    Kof = {name: K for name, K, _, _ in shapes}
+    inputs = sorted({(w, K) for _, K, _, w in shapes})
+    xpool = [{w: torch.from_numpy(workloads.x_gauss_outliers(3, 0, w, s, K)).cuda() for w, K in inputs}
+             for s in range(args.xpool)]
+    ws = B.Workspace(14336, 28672, 2048)
+    stream = torch.cuda.Stream()
+    rows = []
+    wbytes = sum(l.weight_bytes() for l in layers[0].values())
+    for k_chunk in (0, 1, 2, 4, 8, 16, 32, 64, 128):
+        def step(i):
+            xs = xpool[i % args.xpool]
+            for (which, names), grp in zip(order, groups[i % args.layers]):
+                grp.gemv(xs[which], workloads.k_for_kchunk(Kof[names[0]], k_chunk), ws)
+        graphs = {}
+        period = math.lcm(args.layers, args.xpool)
+        for i in range(period):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                step(i)
+            graphs[i] = g
+        for i in range(args.warmup):
+            graphs[i % period].replay()
+        torch.cuda.synchronize()
+        import time
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % period].replay()
+        torch.cuda.synchronize()
+        us_step = (time.perf_counter() - t0) * 1e6 / args.steps
+        ws.set_profiling(args.steps * len(order))
+        for i in range(args.steps):
+            step(i)
+        prof = ws.read_profile()
+        ws.set_profiling(0)
+        rbytes = sum(workloads.k_for_kchunk(K, k_chunk) * N * 2 for _, K, N, _ in shapes)
+        rows.append(dict(k_chunk=k_chunk, k_4096=workloads.k_for_kchunk(4096, k_chunk),
+                         k_14336=workloads.k_for_kchunk(14336, k_chunk), us_per_layer=round(us_step, 1),
+                         us_per_gemv=round(us_step / len(shapes), 2), residual_MB=round(rbytes / 1e6, 2),
+                         gemv_us=round(prof["gemv"][0] * 1e3 / args.steps, 1),
+                         select_us=round(prof["select"][0] * 1e3 / args.steps, 1),
+                         fetch_us=round(prof["fetch"][0] * 1e3 / args.steps, 1),
+                         accumulate_us=round(prof["accumulate"][0] * 1e3 / args.steps, 1),
+                         link_GBs=round(rbytes / max(prof["fetch"][0], 1e-9) * args.steps / 1e6, 1) if k_chunk else 0.0))
+        del graphs
+    base = rows[0]["us_per_layer"]
+    print(f"weights per layer {wbytes / 1e6:.1f} MB; columns: wall us per layer step (graph replay), per-kernel sums per "
+          f"step (eager, kernel timestamps), model = max(base, residual bytes / 57.5 GB/s measured link ceiling)")
+    print(f"{'k_chunk':>7s} {'k(4096)':>8s} {'k(14336)':>9s} {'resid MB':>9s} {'us/layer':>9s} {'us/GEMV':>8s} {'x base':>7s} "
+          f"{'gemv':>7s} {'select':>7s} {'fetch':>7s} {'accum':>7s} {'link GB/s':>9s} {'model us':>9s}")
+    for r in rows:
+        model = max(base, r["residual_MB"] * 1e6 / 57.5e3)
+        print(f"{r['k_chunk']:7d} {r['k_4096']:8d} {r['k_14336']:9d} {r['residual_MB']:9.2f} {r['us_per_layer']:9.1f} "
+              f"{r['us_per_gemv']:8.2f} {r['us_per_layer'] / base:7.2f} {r['gemv_us']:7.1f} {r['select_us']:7.1f} "
+              f"{r['fetch_us']:7.1f} {r['accumulate_us']:7.1f} {r['link_GBs']:9.1f} {model:9.1f}")
+    # knee of the paper's model (Section 5.1) on this machine: k_chunk* = 1024 / R_bw * (b / r)
+    r_bw = 8000.0 / 57.5
+    print(f"paper's knee model with R_bw = 8000 / 57.5 = {r_bw:.0f}, 4-bit weights, fp16 residuals: "
+          f"k_chunk* = 1024 / R_bw * (4 / 16) = {1024 / r_bw * 4 / 16:.2f}")
+    print(json.dumps(rows))
+    ws.close()
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("what", choices=("gemv", "fetch", "ksweep"))
+    ap.add_argument("--reps", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=96)
+    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--layers", type=int, default=4)
+    ap.add_argument("--xpool", type=int, default=8)
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep}[args.what](args)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

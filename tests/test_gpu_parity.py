@@ -188,3 +188,33 @@ def test_multi_rejects_mismatched_matrices(ws):
         dd.decdec_gemv_multi(lin(a, a, a, a, a), x, 0, ws)  # more than 4
     assert e.value.status == -1
     torch.cuda.synchronize()
+
+
+def test_in_kernel_accumulate_equals_separate_kernel_bitwise(ws):
+    """The last producer of a tile adds the partial rows in the same fixed order
+    as the stand-alone accumulate kernel: both modes must agree bit for bit, on
+    every repetition (a visibility bug between the chip's L2 caches would show
+    up as an occasional stale partial row)."""
+    K, N = 4096, 4096
+    p = Problem(workloads.weights(63, 0, 0, K, N), 3)
+    d = p.device()
+    y = torch.empty(N, dtype=torch.float16, device="cuda")
+    xs = [torch.from_numpy(workloads.x_gauss_outliers(63, 0, 0, s, K)).cuda() for s in range(8)]
+    for k in (0, 81):
+        ws.set_inkernel_accumulate(False)
+        want = []
+        for x in xs:
+            dd.decdec_gemv(p.desc, x, d["Wq"], d["scales"], d["zl"], d["R"], None, k, y, ws)
+            torch.cuda.synchronize()
+            want.append(y.clone())
+        ws.set_inkernel_accumulate(True)
+        for rep in range(60):
+            x = xs[rep % len(xs)]
+            y.fill_(float("nan"))
+            dd.decdec_gemv(p.desc, x, d["Wq"], d["scales"], d["zl"], d["R"], None, k, y, ws)
+            if rep % 4 == 0:
+                torch.cuda.synchronize()
+                assert torch.equal(y.view(torch.int16), want[rep % len(xs)].view(torch.int16)), (k, rep)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), want[59 % len(xs)].view(torch.int16))
+    ws.set_inkernel_accumulate(False)
