@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 LINK_PEAK_GBS = 64.0        # PCIe Gen5 x16, one direction (the box reports 32 GT/s x16)
+# HBM bytes per base-GEMV launch from rocprofv3 --pmc (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain
+# copy kernel of known size gives; profiles/gemv_kernel_hbm_traffic_pmc.md), summed over the four launches of a step
+# of the default workload.  Only valid for that workload; other settings report null.
+PMC_TRAFFIC_BYTES_PER_STEP = 89.08e6 + 1.25e6
 K_FRACTION = 0.02
 CFG = 2                     # BASELINE config index used for seeding (configs[1])
 
@@ -202,7 +206,8 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": round(PMC_TRAFFIC_BYTES_PER_STEP / n_calls) if args.grouping == "grouped" else None,
+            "algorithmic_bytes_per_launch": round(gemv_bytes / n_calls),
             "avg_launch_us": round(g_ms * 1e3 / max(g_n, 1), 3),
             "achieved_without_compensation": round(gemv_gbs_alone, 1),
             "avg_launch_us_without_compensation": round(gb_ms * 1e3 / max(gb_n, 1), 3),
