@@ -170,7 +170,6 @@ def main() -> int:
     f_ms, f_n = prof["fetch"]
     s_ms, s_n = prof["select"]
     gb_ms, gb_n = prof_base["gemv"]
-    gemv_gbs = gemv_bytes * args.steps / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
     gemv_gbs_alone = gemv_bytes * args.steps / (gb_ms * 1e-3) / 1e9 if gb_ms > 0 else 0.0
     fetch_gbs = fetch_bytes * args.steps / (f_ms * 1e-3) / 1e9 if f_ms > 0 else 0.0
 
@@ -200,25 +199,27 @@ def main() -> int:
         "base_only_us_per_gemv": round(ms_base * 1e3 / len(shapes), 3),
         "compensation_added_pct": round((ms_step / ms_base - 1.0) * 100.0, 1),
         "roofline": {
-            "kernel": f"gemv_kernel<PACK_U3> (base GEMV, {n_calls} launches per step)",
+            "kernel": f"gemv_kernel<PACK_U3> (base GEMV, {n_calls} launches per step; timed on the base-only steps of this "
+                      "run: in a compensated step the same device code runs inside compensated_gemv_kernel, whose "
+                      "duration is set by the host link)",
             "bound": "hbm",
-            "achieved": round(gemv_gbs, 1),
+            "achieved": round(gemv_gbs_alone, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
+            "frac": round(gemv_gbs_alone / HBM_PEAK_GBS, 4),
             "traffic": round(PMC_TRAFFIC_BYTES_PER_STEP / n_calls) if args.grouping == "grouped" else None,
             "algorithmic_bytes_per_launch": round(gemv_bytes / n_calls),
-            "avg_launch_us": round(g_ms * 1e3 / max(g_n, 1), 3),
-            "achieved_without_compensation": round(gemv_gbs_alone, 1),
-            "avg_launch_us_without_compensation": round(gb_ms * 1e3 / max(gb_n, 1), 3),
+            "avg_launch_us": round(gb_ms * 1e3 / max(gb_n, 1), 3),
         },
         "link_roofline": {
-            "kernel": f"fetch_fp16_kernel (zero-copy residual fetch + residual GEMV, {n_calls} launches per step)",
+            "kernel": f"compensated_gemv_kernel<PACK_U3, fp16 rows> (selection + zero-copy residual fetch + residual GEMV "
+                      f"in its first workgroups, base GEMV in the others; {n_calls} launches per step)",
             "bound": "host_link",
             "achieved": round(fetch_gbs, 2),
             "peak": LINK_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(fetch_gbs / LINK_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": round(fetch_bytes / n_calls),
             "avg_launch_us": round(f_ms * 1e3 / max(f_n, 1), 3),
         },
         "select_avg_us": round(s_ms * 1e3 / max(s_n, 1), 3),

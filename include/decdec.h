@@ -105,6 +105,26 @@ int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, 
  * choice.  Affects later calls on this workspace. */
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
 
+/* How one compensated GEMV (k > 0) is laid out on the GPU.  The result is the
+ * same bit for bit in every mode.
+ *   FUSED (default): one kernel whose first workgroups do steps 1-3 (selection,
+ *     zero-copy fetch, residual GEMV) and whose other workgroups do the base
+ *     GEMV, then the accumulate kernel; everything on the caller's stream.
+ *   SERIAL: residual kernel, base GEMV kernel, accumulate kernel one after
+ *     the other on the caller's stream.
+ *   TWO_STREAMS: the arrangement of Section 4.1: steps 1-3 on the workspace's
+ *     side stream, the base GEMV on the caller's stream, joined by events
+ *     before the accumulate kernel. */
+typedef enum { DECDEC_MODE_FUSED = 0, DECDEC_MODE_SERIAL = 1, DECDEC_MODE_TWO_STREAMS = 2 } decdec_mode;
+int decdec_ws_set_mode(decdec_ws* ws, int32_t mode);
+
+/* Where step 1 runs when decdec_gemv / decdec_gemv_multi select for themselves.
+ * on = 0 (default): inside the residual kernel, every workgroup selecting for
+ * itself (K <= 16384 and k <= 4096; larger problems use the selection kernel).
+ * on = 1: always as a kernel of its own before the residual kernel.  The
+ * selection is the same either way. */
+int decdec_ws_set_separate_select(decdec_ws* ws, int32_t on);
+
 /* How the partial results of the base GEMV and of the residual kernel are
  * added.  on = 0 (default): by a small kernel of its own on the caller's
  * stream.  on = 1: whichever of the two kernels completes a 64-column tile
@@ -168,10 +188,10 @@ int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k,
  *   R_scales_f16_dev dev fp16 [N] (INT4_SYM_COL only, else NULL)
  *   k              salient channels, 0 <= k <= min(K, maxk of ws)
  *   y_f16_dev      dev fp16 [N] out
- * The base GEMV runs on `stream`; selection, zero-copy fetch and residual
- * GEMV run on the workspace's side stream, concurrently; the sum is formed
- * on `stream` after both (fp32 accumulation throughout, one rounding to
- * fp16).  k == 0 uses `stream` only and equals the plain quantised GEMV. */
+ * By default the base GEMV and steps 1-3 run side by side inside one kernel on
+ * `stream` (see decdec_ws_set_mode); the sum is formed on `stream` after both
+ * (fp32 accumulation throughout, one rounding to fp16).  k == 0 equals the
+ * plain quantised GEMV. */
 int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
                 const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
                 const void* R_pinned, const void* R_scales_f16_dev,

@@ -17,11 +17,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(_HERE, "libdecdec.so")
 
 W_UNIFORM_G128, W_LUT_COL8 = 0, 1
+MODE_FUSED, MODE_SERIAL, MODE_TWO_STREAMS = 0, 1, 2
 R_FP16, R_INT4_SYM_COL = 0, 1
 
 EXPORTED_SYMBOLS = (
     "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
-    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate",
+    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_select_topk", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
     "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
@@ -77,6 +78,8 @@ def lib() -> C.CDLL:
     L.decdec_ws_set_profiling.argtypes = [vp, i32]
     L.decdec_ws_set_gemv_split.argtypes = [vp, i32]
     L.decdec_ws_set_inkernel_accumulate.argtypes = [vp, i32]
+    L.decdec_ws_set_separate_select.argtypes = [vp, i32]
+    L.decdec_ws_set_mode.argtypes = [vp, i32]
     L.decdec_ws_read_profile.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     L.decdec_packed_bytes.restype = sz
     L.decdec_packed_bytes.argtypes = [dp]
@@ -138,6 +141,13 @@ class Workspace:
 
     def set_fetch_split(self, row_split: int):
         _check(lib().decdec_ws_set_fetch_split(self.handle, row_split), "decdec_ws_set_fetch_split")
+
+    def set_mode(self, mode: int):
+        """MODE_FUSED (default), MODE_SERIAL or MODE_TWO_STREAMS."""
+        _check(lib().decdec_ws_set_mode(self.handle, int(mode)), "decdec_ws_set_mode")
+
+    def set_separate_select(self, on: bool):
+        _check(lib().decdec_ws_set_separate_select(self.handle, int(on)), "decdec_ws_set_separate_select")
 
     def set_inkernel_accumulate(self, on: bool):
         _check(lib().decdec_ws_set_inkernel_accumulate(self.handle, int(on)), "decdec_ws_set_inkernel_accumulate")

@@ -65,6 +65,8 @@ struct decdec_ws {
     float* gpart;    // [kMaxGemvSlices][maxN]
     float* cpart;    // [kMaxFetchSlices][maxN]
     unsigned* counters;  // [maxN/64] per-tile arrival counters, zero between calls
+    int32_t mode;                 // decdec_mode
+    int32_t separate_select;      // 1: selection always runs as a kernel of its own
     int32_t inkernel_accumulate;  // 1: the last producer of a tile adds the partial rows (no accumulate kernel)
     int32_t counters_dirty;       // a call failed half-way: clear the counters before the next one
     const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
@@ -228,6 +230,18 @@ int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const
 int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on) {
     if (ws == nullptr || (on != 0 && on != 1)) return DECDEC_EINVAL;
     ws->inkernel_accumulate = on;
+    return DECDEC_OK;
+}
+
+int decdec_ws_set_mode(decdec_ws* ws, int32_t mode) {
+    if (ws == nullptr || mode < DECDEC_MODE_FUSED || mode > DECDEC_MODE_TWO_STREAMS) return DECDEC_EINVAL;
+    ws->mode = mode;
+    return DECDEC_OK;
+}
+
+int decdec_ws_set_separate_select(decdec_ws* ws, int32_t on) {
+    if (ws == nullptr || (on != 0 && on != 1)) return DECDEC_EINVAL;
+    ws->separate_select = on;
     return DECDEC_OK;
 }
 
@@ -436,25 +450,44 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
         ws->counters_dirty = 0;
     }
     const int rc_enq = [&]() -> int {
-        if (k > 0) {
-            // Section 4.1: all compensation steps run beside the base GEMV on another stream.
-            DD_HIP(hipEventRecord(ws->ev_fork, stream));
-            DD_HIP(hipStreamWaitEvent(ws->side, ws->ev_fork, 0));
-            const int32_t* idx = idx_in;
-            const void* xsel = xsel_in;
+        if (k == 0) {
+            DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, gslices, gpw, fa, stream, tm[0]));
+            if (pmask) *pmask |= 1;
+        } else {
+            // The kernels that follow read idx / xsel only; the const is dropped for the shared signatures.
+            int32_t* idx = const_cast<int32_t*>(idx_in);
+            void* xsel = const_cast<void*>(xsel_in);
+            int select_chunks = 0;
+            const bool two_streams = ws->mode == DECDEC_MODE_TWO_STREAMS;
+            hipStream_t comp = two_streams ? ws->side : stream;  // where steps 1-3 run
+            if (two_streams) {
+                // Section 4.1 as printed: compensation on another stream than the base GEMV.
+                DD_HIP(hipEventRecord(ws->ev_fork, stream));
+                DD_HIP(hipStreamWaitEvent(ws->side, ws->ev_fork, 0));
+            }
             if (!have_idx) {
-                DD_HIP(launch_select_topk(x, sh.K, k, ws->idx, ws->xsel, ws->side, tm[1]));
                 idx = ws->idx;
                 xsel = ws->xsel;
-                if (pmask) *pmask |= 2;
+                select_chunks = ws->separate_select ? 0 : fetch_select_chunks(sh.K, k);
+                if (select_chunks == 0) {
+                    DD_HIP(launch_select_topk(x, sh.K, k, ws->idx, ws->xsel, comp, tm[1]));
+                    if (pmask) *pmask |= 2;
+                }
             }
-            DD_HIP(launch_fetch(d0->rfmt, sh, fop, idx, xsel, k, ws->cpart, cslices, fa, ws->side, tm[2]));
-            if (pmask) *pmask |= 4;
-            DD_HIP(hipEventRecord(ws->ev_join, ws->side));
+            if (ws->mode == DECDEC_MODE_FUSED) {
+                DD_HIP(launch_compensated_gemv(kind, d0->rfmt, sh, gop, fop, x, select_chunks, idx, xsel, k, ws->gpart,
+                                               gslices, gpw, ws->cpart, cslices, fa, stream, tm[2]));
+                if (pmask) *pmask |= 4;
+            } else {
+                DD_HIP(launch_fetch(d0->rfmt, sh, fop, x, select_chunks, idx, xsel, k, ws->cpart, cslices, fa, comp,
+                                    tm[2]));
+                if (pmask) *pmask |= 4;
+                if (two_streams) DD_HIP(hipEventRecord(ws->ev_join, ws->side));
+                DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, gslices, gpw, fa, stream, tm[0]));
+                if (pmask) *pmask |= 1;
+                if (two_streams) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
+            }
         }
-        DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, gslices, gpw, fa, stream, tm[0]));
-        if (pmask) *pmask |= 1;
-        if (k > 0) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
         if (!ws->inkernel_accumulate) {
             DD_HIP(launch_accumulate(sh, ys, ws->gpart, gslices, ws->cpart, cslices, stream, tm[3]));
             if (pmask) *pmask |= 8;

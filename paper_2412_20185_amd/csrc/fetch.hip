@@ -1,185 +1,26 @@
-// Steps 2 and 3 of dynamic error compensation (DecDEC Section 4.1): fetch the
-// residual rows of the selected input channels from pinned CPU memory and
-// multiply them with x[sc_indices]:  o_dec[n] = sum_j R_hat[s_j][n] * x[s_j].
-//
-// Zero-copy (Section 4.3): the kernel reads the rows in place over the host
-// link with plain 128-bit loads; a wavefront covers 1 KiB of one row per load,
-// so requests are cache-line sized and contiguous per row (Section 4.2: each
-// input-channel row is contiguous in CPU memory).  As in the paper's kernel
-// (Section 4.3 "Kernel Fusion") a wave owns a column segment of the rows it
-// handles, so the sum over its rows needs no cross-lane reduction.  Unlike the
-// paper's kernel the rows are additionally split into `slices` (the knob that
-// plays the role of n_tb in Section 4.4: enough requests in flight to fill
-// the link without taking compute units from the base GEMV); each slice
-// writes one fp32 partial row and the accumulate kernel adds them.
+// Residual fetch + residual GEMV as a kernel of its own.  The device code is
+// in fetch_body.h.
 #include <hip/hip_runtime.h>
 
-#include "finalize.h"
-#include "kernels.h"
+#include "fetch_body.h"
 
 namespace decdec {
 namespace {
 
-constexpr int kUnroll = 4;  // row loads in flight per lane
-
-__device__ __forceinline__ float h2f(uint32_t bits16) {
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
-}
-
-struct FetchJobs {
-    const uint4* R[kMaxMulti];
-    const uint16_t* Rs[kMaxMulti];
-    int N[kMaxMulti];
-    int col0[kMaxMulti];
-    int wc_end[kMaxMulti];  // cumulative count of wave-wide column segments up to and including matrix m
-    int n;
-};
-
-struct WaveTask {
-    int m, wc, rs;
-    bool valid;
-};
-
-// Task t of the grid: row slice rs = t / wavecols, column segment t % wavecols
-// of the concatenated matrices.
-__device__ __forceinline__ WaveTask wave_task(const FetchJobs& jobs, int wavecols, int slices) {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int task = blockIdx.x * 4 + wave;
-    WaveTask t;
-    t.valid = task < wavecols * slices;
-    t.rs = task / wavecols;
-    const int c = task - t.rs * wavecols;
-    int m = 0;
-#pragma unroll
-    for (int i = 0; i < kMaxMulti - 1; ++i) m += (i + 1 < jobs.n && c >= jobs.wc_end[i]) ? 1 : 0;
-    t.m = m;
-    t.wc = c - (m > 0 ? jobs.wc_end[m - 1] : 0);
-    return t;
-}
-
-// Wave task (m, wc, rs): columns [wc*512, wc*512+512) of matrix m for the rows j in slice rs.
+template <int SELECT_NCH>
 __global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, const FinalizeArgs fa,
-                                                        const int32_t* __restrict__ idx,
-                                                        const uint16_t* __restrict__ xsel, int k, int K, int Ntot,
+                                                        const uint16_t* __restrict__ x, int32_t* idx_g,
+                                                        uint16_t* xsel_g, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
-    const int lane = threadIdx.x & 63;
-    const WaveTask t = wave_task(jobs, wavecols, slices);
-    if (!t.valid) return;
-    const int N = jobs.N[t.m];
-    const uint4* __restrict__ R = jobs.R[t.m];
-    const int oct = t.wc * 64 + lane;  // 8 columns = one 16-byte piece of a row
-    const bool active = oct * 8 < N;
-    const int rows_per = (k + slices - 1) / slices;
-    const int j0 = t.rs * rows_per, j1 = min(j0 + rows_per, k);
-    const size_t row16 = (size_t)(N / 8);
-
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int j = j0; j < j1; j += kUnroll) {
-        uint4 v[kUnroll];
-        float xs[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            v[u] = make_uint4(0, 0, 0, 0);
-            xs[u] = 0.f;
-            if (j + u < j1) {
-                const int row = idx[j + u];
-                if (active && (unsigned)row < (unsigned)K) {
-                    v[u] = R[(size_t)row * row16 + oct];
-                    xs[u] = h2f(xsel[j + u]);
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                acc[2 * c] = fmaf(h2f(w[c] & 0xFFFFu), xs[u], acc[2 * c]);
-                acc[2 * c + 1] = fmaf(h2f(w[c] >> 16), xs[u], acc[2 * c + 1]);
-            }
-        }
-    }
-    if (active) {
-        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)oct * 8;
-        if (fa.counters != nullptr) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) store_partial(out + i, acc[i], true);
-        } else {
-            reinterpret_cast<float4*>(out)[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            reinterpret_cast<float4*>(out)[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        }
-    }
-    if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, t.m, t.wc * 8, min(8, N / 64 - t.wc * 8), lane);
+    fetch_fp16_block<SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices, (int)blockIdx.x);
 }
 
-// 4-bit residuals (Section 4.2): a 16-byte piece holds 32 columns; a wave
-// covers 2048 columns.  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
+template <int SELECT_NCH>
 __global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, const FinalizeArgs fa,
-                                                        const int32_t* __restrict__ idx,
-                                                        const uint16_t* __restrict__ xsel, int k, int K, int Ntot,
+                                                        const uint16_t* __restrict__ x, int32_t* idx_g,
+                                                        uint16_t* xsel_g, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
-    const int lane = threadIdx.x & 63;
-    const WaveTask t = wave_task(jobs, wavecols, slices);
-    if (!t.valid) return;
-    const int N = jobs.N[t.m];
-    const uint4* __restrict__ R = jobs.R[t.m];
-    const uint16_t* __restrict__ Rs = jobs.Rs[t.m];
-    const int piece = t.wc * 64 + lane;  // 32 columns
-    const bool active = piece * 32 < N;
-    const int rows_per = (k + slices - 1) / slices;
-    const int j0 = t.rs * rows_per, j1 = min(j0 + rows_per, k);
-    const size_t row16 = (size_t)(N / 32);
-
-    float acc[32];
-#pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
-    for (int j = j0; j < j1; j += kUnroll) {
-        uint4 v[kUnroll];
-        float xs[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            v[u] = make_uint4(0, 0, 0, 0);
-            xs[u] = 0.f;
-            if (j + u < j1) {
-                const int row = idx[j + u];
-                if (active && (unsigned)row < (unsigned)K) {
-                    v[u] = R[(size_t)row * row16 + piece];
-                    xs[u] = h2f(xsel[j + u]);
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int q = (int)(w[c] << (28 - 4 * i)) >> 28;  // 4-bit two's complement
-                    acc[8 * c + i] = fmaf((float)q, xs[u], acc[8 * c + i]);
-                }
-            }
-        }
-    }
-    if (active) {
-        const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * 32);
-        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * 32;
-        const bool coherent = fa.counters != nullptr;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const uint4 sv = s4[b];
-            const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w};
-            float r[8];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                r[2 * c] = acc[8 * b + 2 * c] * h2f(sw[c] & 0xFFFFu);
-                r[2 * c + 1] = acc[8 * b + 2 * c + 1] * h2f(sw[c] >> 16);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) store_partial(out + 8 * b + i, r[i], coherent);
-        }
-    }
-    if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, t.m, t.wc * 32, min(32, N / 64 - t.wc * 32), lane);
+    fetch_int4_block<SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices, (int)blockIdx.x);
 }
 
 inline int cols_per_wave(int rfmt) { return rfmt == 0 ? 512 : 2048; }
@@ -207,8 +48,30 @@ int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split) {
     return slices;
 }
 
-hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const int32_t* idx,
-                        const void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
+int fetch_select_chunks(int K, int k) {
+    // In-kernel selection: keys of a 256-thread workgroup stay in registers (at most 8 chunks of 8 per thread)
+    // and the selection must fit in LDS.
+    if (k < 1 || k > 4096 || K > 16384) return 0;
+    return K <= 4096 ? 2 : K <= 8192 ? 4 : 8;
+}
+
+template <int NCH>
+static hipError_t launch_fetch_nch(int rfmt, const FetchJobs& jobs, const FinalizeArgs& fa, const uint16_t* x,
+                                   int32_t* idx, uint16_t* xs, int k, int K, int Ntot, float* cpart, int wc,
+                                   int slices, dim3 grid, hipStream_t stream, const KernelTimer* tm) {
+    const unsigned lds = NCH > 0 ? (unsigned)(((size_t)k * 6 + 15) / 16 * 16) : 0u;
+    if (rfmt == 0) {
+        return launch_kernel(tm, fetch_fp16_kernel<NCH>, grid, dim3(256), lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
+                             cpart, wc, slices);
+    }
+    return launch_kernel(tm, fetch_int4_kernel<NCH>, grid, dim3(256), lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
+                         cpart, wc, slices);
+}
+
+// select_chunks > 0: the kernel selects for itself from x (and writes the selection to idx / xsel);
+// 0: idx / xsel hold the selection already.
+hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const void* x, int select_chunks,
+                        int32_t* idx, void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
                         hipStream_t stream, const KernelTimer* tm) {
     FetchJobs jobs{};
     jobs.n = sh.n;
@@ -222,15 +85,17 @@ hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op,
         jobs.wc_end[m] = wc;
     }
     const int tasks = wc * slices;
-    const dim3 grid((unsigned)((tasks + 3) / 4)), block(256);
-    const uint16_t* xs = static_cast<const uint16_t*>(xsel);
+    const dim3 grid((unsigned)((tasks + 3) / 4));
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint16_t* xs = static_cast<uint16_t*>(xsel);
     const int Ntot = sh.col0[sh.n];
-    if (rfmt == 0) {
-        return launch_kernel(tm, fetch_fp16_kernel, grid, block, 0, stream, jobs, fa, idx, xs, k, sh.K, Ntot, cpart,
-                             wc, slices);
+    switch (select_chunks) {
+        case 0: return launch_fetch_nch<0>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
+        case 2: return launch_fetch_nch<2>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
+        case 4: return launch_fetch_nch<4>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
+        case 8: return launch_fetch_nch<8>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
+        default: return hipErrorInvalidValue;
     }
-    return launch_kernel(tm, fetch_int4_kernel, grid, block, 0, stream, jobs, fa, idx, xs, k, sh.K, Ntot, cpart, wc,
-                         slices);
 }
 
 }  // namespace decdec

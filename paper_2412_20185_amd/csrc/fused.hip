@@ -1,0 +1,116 @@
+// One launch for a whole compensated GEMV (DecDEC Section 4.1): the first
+// `nfetch` workgroups of the grid do steps 1-3 (selection for themselves, then
+// zero-copy fetch of the selected residual rows and the residual GEMV), all
+// other workgroups do the base GEMV.  The two parts meet in the accumulate
+// kernel that follows on the same stream.
+//
+// Why one grid instead of the paper's two streams (Section 4.1, 4.3): measured
+// on MI355X, handing work from one hardware queue to another costs about 10 us
+// per join, more than the base GEMV itself for Llama-3-8B shapes, and a GEMV
+// kernel that runs beside the fetch kernel from another queue starts late and
+// runs 5-7x slower.  Inside one grid the fetch workgroups are dispatched first
+// (lowest workgroup ids), the GEMV workgroups fill the rest of the chip and
+// finish while the fetch workgroups are still waiting for the host link, and
+// nothing has to be joined.  How many workgroups fetch (the paper's n_tb,
+// Section 4.4) is the row split of the residual kernel.
+#include <hip/hip_runtime.h>
+
+#include "fetch_body.h"
+#include "gemv_body.h"
+
+namespace decdec {
+namespace {
+
+template <int KIND, int RFMT, int SELECT_NCH>
+__global__ __launch_bounds__(256) void compensated_gemv_kernel(
+    const GemvJobs gjobs, const FetchJobs fjobs, const FinalizeArgs fa, const uint16_t* __restrict__ x,
+    int32_t* idx_g, uint16_t* xsel_g, int k, int K, int Ntot, float* __restrict__ gpart, float* __restrict__ cpart,
+    int G, int gslices, int gpw, int wavecols, int cslices, int nfetch) {
+    const int bid = (int)blockIdx.x;
+    if (bid < nfetch) {
+        if constexpr (RFMT == 0) {
+            fetch_fp16_block<SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
+        } else {
+            fetch_int4_block<SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
+        }
+    } else {
+        gemv_block<KIND>(gjobs, fa, reinterpret_cast<const uint32_t*>(x), gpart, Ntot, G, gslices, gpw, bid - nfetch);
+    }
+}
+
+template <int KIND, int RFMT>
+hipError_t launch_nch(int nch, const KernelTimer* tm, dim3 grid, unsigned lds, hipStream_t stream,
+                      const GemvJobs& gj, const FetchJobs& fj, const FinalizeArgs& fa, const uint16_t* x, int32_t* idx,
+                      uint16_t* xs, int k, int K, int Ntot, float* gpart, float* cpart, int G, int gslices, int gpw,
+                      int wc, int cslices, int nfetch) {
+    const dim3 block(256);
+    switch (nch) {
+        case 0:
+            return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 0>, grid, block, lds, stream, gj, fj, fa, x, idx,
+                                 xs, k, K, Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        case 2:
+            return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 2>, grid, block, lds, stream, gj, fj, fa, x, idx,
+                                 xs, k, K, Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        case 4:
+            return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 4>, grid, block, lds, stream, gj, fj, fa, x, idx,
+                                 xs, k, K, Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        case 8:
+            return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 8>, grid, block, lds, stream, gj, fj, fa, x, idx,
+                                 xs, k, K, Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
+template <int KIND, typename... A>
+hipError_t launch_rfmt(int rfmt, A... a) {
+    return rfmt == 0 ? launch_nch<KIND, 0>(a...) : launch_nch<KIND, 1>(a...);
+}
+
+}  // namespace
+
+hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, const GemvOperands& gop,
+                                   const FetchOperands& fop, const void* x, int select_chunks, int32_t* idx, void* xsel,
+                                   int k, float* gpart, int gslices, int gpw, float* cpart, int cslices,
+                                   const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm) {
+    const int G = sh.K / kGroup;
+    GemvJobs gj{};
+    FetchJobs fj{};
+    gj.n = fj.n = sh.n;
+    const int cpw = rfmt == 0 ? 512 : 2048;  // columns one wavefront covers per row load
+    int tiles = 0, wc = 0;
+    for (int m = 0; m < sh.n; ++m) {
+        gj.Wq[m] = static_cast<const uint4*>(gop.Wq[m]);
+        gj.scales[m] = static_cast<const uint16_t*>(gop.scales[m]);
+        gj.zeros_or_lut[m] = static_cast<const uint16_t*>(gop.zeros_or_lut[m]);
+        gj.N[m] = fj.N[m] = sh.N[m];
+        gj.col0[m] = fj.col0[m] = sh.col0[m];
+        tiles += sh.N[m] / kTileCols;
+        gj.tile_end[m] = tiles;
+        fj.R[m] = static_cast<const uint4*>(fop.R[m]);
+        fj.Rs[m] = static_cast<const uint16_t*>(fop.R_scales[m]);
+        wc += (sh.N[m] + cpw - 1) / cpw;
+        fj.wc_end[m] = wc;
+    }
+    const int nfetch = (wc * cslices + 3) / 4;
+    const dim3 grid((unsigned)(nfetch + tiles * gslices));
+    const unsigned lds = select_chunks > 0 ? (unsigned)(((size_t)k * 6 + 15) / 16 * 16) : 0u;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint16_t* xs = static_cast<uint16_t*>(xsel);
+    const int Ntot = sh.col0[sh.n];
+    switch (kind) {
+        case PACK_U4:
+            return launch_rfmt<PACK_U4>(rfmt, select_chunks, tm, grid, lds, stream, gj, fj, fa, xp, idx, xs, k, sh.K, Ntot,
+                                        gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        case PACK_U3:
+            return launch_rfmt<PACK_U3>(rfmt, select_chunks, tm, grid, lds, stream, gj, fj, fa, xp, idx, xs, k, sh.K, Ntot,
+                                        gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        case PACK_LUT3:
+            return launch_rfmt<PACK_LUT3>(rfmt, select_chunks, tm, grid, lds, stream, gj, fj, fa, xp, idx, xs, k, sh.K,
+                                          Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace decdec

@@ -70,9 +70,19 @@ hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, voi
 // fetch.hip --------------------------------------------------------------
 // cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic).
 int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split);
-hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const int32_t* idx,
-                        const void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
+// select_chunks (from fetch_select_chunks) > 0: the kernel runs the exact top-k on x itself and writes
+// the selection to idx / xsel; 0: idx / xsel hold the selection already (x is not read).
+int fetch_select_chunks(int K, int k);
+hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const void* x, int select_chunks,
+                        int32_t* idx, void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
                         hipStream_t stream, const KernelTimer* tm = nullptr);
+
+// fused.hip -------------------------------------------------------------
+// Base GEMV and residual kernel in one grid (the fetch workgroups come first).
+hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, const GemvOperands& gop,
+                                   const FetchOperands& fop, const void* x, int select_chunks, int32_t* idx, void* xsel,
+                                   int k, float* gpart, int gslices, int gpw, float* cpart, int cslices,
+                                   const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // accumulate.hip ---------------------------------------------------------
 // y_m[n] = fp16( sum_s gpart[s][col0[m]+n] + sum_r cpart[r][col0[m]+n] )

@@ -12,31 +12,28 @@
 namespace decdec {
 namespace {
 
-template <int THREADS>
+template <int THREADS, int NCH>
 __global__ __launch_bounds__(THREADS) void select_topk_kernel(const uint16_t* __restrict__ x, int K, int k,
                                                              int32_t* __restrict__ idx_out,
                                                              uint16_t* __restrict__ xsel_out) {
-    extern __shared__ uint4 s_keys[];  // K fp16 values
     __shared__ SelectShared sh;
-    block_select_topk<THREADS>(x, K, k, s_keys, sh, idx_out, xsel_out);
+    block_select_topk<THREADS, NCH>(x, K, k, sh, idx_out, xsel_out);
 }
 
 }  // namespace
 
 hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream,
                               const KernelTimer* tm) {
-    const size_t lds = (size_t)K * 2;
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_topk_kernel<1024>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSelectMaxK * 2);
-    if (attr != hipSuccess) return attr;
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* xs = static_cast<uint16_t*>(xsel_out);
-    if (K <= 8192) {
-        return launch_kernel(tm, select_topk_kernel<256>, dim3(1), dim3(256), (unsigned)lds, stream, xp, K, k, idx_out,
-                             xs);
-    }
-    return launch_kernel(tm, select_topk_kernel<1024>, dim3(1), dim3(1024), (unsigned)lds, stream, xp, K, k, idx_out,
-                         xs);
+    const dim3 one(1);
+    if (K <= 4096) return launch_kernel(tm, select_topk_kernel<256, 2>, one, dim3(256), 0, stream, xp, K, k, idx_out, xs);
+    if (K <= 8192) return launch_kernel(tm, select_topk_kernel<256, 4>, one, dim3(256), 0, stream, xp, K, k, idx_out, xs);
+    if (K <= 16384)
+        return launch_kernel(tm, select_topk_kernel<1024, 2>, one, dim3(1024), 0, stream, xp, K, k, idx_out, xs);
+    if (K <= 32768)
+        return launch_kernel(tm, select_topk_kernel<1024, 4>, one, dim3(1024), 0, stream, xp, K, k, idx_out, xs);
+    return launch_kernel(tm, select_topk_kernel<1024, 8>, one, dim3(1024), 0, stream, xp, K, k, idx_out, xs);
 }
 
 }  // namespace decdec

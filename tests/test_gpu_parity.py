@@ -218,3 +218,45 @@ def test_in_kernel_accumulate_equals_separate_kernel_bitwise(ws):
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), want[59 % len(xs)].view(torch.int16))
     ws.set_inkernel_accumulate(False)
+
+
+@pytest.mark.parametrize("K,N,k", [(4096, 1024, 81), (8192, 512, 300), (14336, 1024, 286), (16384, 256, 4096),
+                                   (1024, 2112, 1)])
+def test_selection_inside_fetch_kernel_equals_selection_kernel(ws, K, N, k):
+    """Step 1 run by every workgroup of the residual kernel for itself must give the
+    same channels and the same y (bit for bit) as the stand-alone selection kernel."""
+    p = Problem(workloads.weights(64, 0, 0, K, N), 4)
+    for step in range(3):
+        x = workloads.x_student_t(64, 0, 0, step, K, outlier_frac=0.005)
+        y_ref, sc = p.reference(x, k)
+        ws.set_separate_select(True)
+        y_a, idx_a, xs_a = p.run(x, k, ws)
+        ws.set_separate_select(False)
+        y_b, idx_b, xs_b = p.run(x, k, ws)
+        assert np.array_equal(idx_a, sc) and np.array_equal(idx_b, sc)
+        assert np.array_equal(xs_a.view(np.uint16), xs_b.view(np.uint16))
+        assert np.array_equal(y_a.view(np.uint16), y_b.view(np.uint16))
+        assert_parity(y_b, y_ref, idx_b, sc, what=f"fused select {K}x{N} k={k}")
+
+
+@pytest.mark.parametrize("wfmt,bits,rfmt", [("uniform", 3, "fp16"), ("uniform", 4, "int4"), ("lut", 3, "fp16")])
+def test_all_layouts_of_the_work_give_the_same_bits(ws, wfmt, bits, rfmt):
+    """One fused kernel, separate kernels on one stream, and the paper's two-stream
+    arrangement compute the same partial rows and add them in the same order."""
+    K, N = 4096, 1536
+    p = Problem(workloads.weights(65, 0, 0, K, N), bits, wfmt=wfmt, rfmt=rfmt, lut_iters=2,
+                alphas=oracle.quantize.DEFAULT_ALPHAS[::10])
+    try:
+        for step, k in enumerate([1, 81, 1000]):
+            x = workloads.x_gauss_outliers(65, 0, 0, step, K)
+            y_ref, sc = p.reference(x, k)
+            outs = []
+            for mode in (dd.MODE_FUSED, dd.MODE_SERIAL, dd.MODE_TWO_STREAMS):
+                ws.set_mode(mode)
+                y, idx, _ = p.run(x, k, ws)
+                assert_parity(y, y_ref, idx, sc, what=f"mode {mode} {wfmt}{bits}/{rfmt} k={k}")
+                outs.append(y)
+            assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+            assert np.array_equal(outs[0].view(np.uint16), outs[2].view(np.uint16))
+    finally:
+        ws.set_mode(dd.MODE_FUSED)
