@@ -178,6 +178,24 @@ int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint
 int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k,
                        int32_t* idx_out_dev, void* xsel_f16_dev, void* stream);
 
+/* Step 1 as the paper's kernel does it (Section 4.3, fast approximate Top-K):
+ * x is cut into chunks of 1024 channels and every chunk contributes k_chunk
+ * channels.  Inside a chunk |x| is scattered into 32 buckets with boundaries
+ *   b_i = b0 - i (b0 - b15) / 15  (0 <= i <= 15),  b_i = b15 (31 - i) / 16  (15 <= i <= 30),
+ * bucket 0 = |x| >= b0, bucket 31 = |x| < b_30; channels are gathered from
+ * bucket 0 upwards and the bucket that overflows gives its lowest indices (the
+ * paper picks at random there).  b0 >= b15 >= 0 come from calibration: b15 the
+ * largest k-th largest |x| over calibration vectors, b0 the largest |x| seen.
+ * The bucket of a value is computed in fp32 as
+ *   |x| >= b0: 0;  |x| >= b15: clamp(ceil((b0 - |x|) / ((b0 - b15) / 15)), 1, 15);
+ *   else: 31 - clamp(floor(|x| / (b15 / 16)), 0, 15).
+ *   x_f16_dev: dev fp16 [K], 16-byte aligned, K a multiple of 1024; 0 <= k_chunk <= 1024.
+ *   idx_out_dev: dev int32 [k_chunk * K / 1024], chunk after chunk, ascending
+ *   inside a chunk (hence ascending overall); xsel_f16_dev: fp16 of the same
+ *   length or NULL.  Feed the result to decdec_gemv_idx.  k_chunk == 0 enqueues nothing. */
+int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, float b0, float b15,
+                         int32_t* idx_out_dev, void* xsel_f16_dev, void* stream);
+
 /* The whole path (Section 4.1 steps 1-4 beside the base GEMV):
  *   y = W_hat x + R_hat[sc,:]^T x[sc],  sc = top-k of |x|.
  *   x_f16_dev      dev fp16 [K]

@@ -27,4 +27,7 @@ from .quantize import (  # noqa: F401
     residual_fp16, quantize_residual_int4, dequantize_residual_int4,
 )
 from .select import topk_abs, magnitude_keys  # noqa: F401
+from .bucket_select import (  # noqa: F401
+    bucket_boundaries, bucket_index, topk_bucket, calibrate_boundaries, recall,
+)
 from .gemv import compensated_gemv, compensated_gemv_columns, error_metric  # noqa: F401

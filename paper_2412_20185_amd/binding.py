@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
     "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
-    "decdec_pack_residual_int4", "decdec_select_topk", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
+    "decdec_pack_residual_int4", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
     "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
 )
 
@@ -87,6 +87,7 @@ def lib() -> C.CDLL:
     L.decdec_unpack_weights.argtypes = [dp, vp, vp]
     L.decdec_pack_residual_int4.argtypes = [i32, i32, vp, vp]
     L.decdec_select_topk.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.decdec_select_bucket.argtypes = [vp, i32, i32, C.c_float, C.c_float, vp, vp, vp]
     L.decdec_gemv.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     L.decdec_gemv_idx.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     L.decdec_quantize_uniform.argtypes = [dp, vp, vp, vp, vp, vp, vp]
@@ -225,6 +226,11 @@ def decdec_pack_residual_int4(codes_KN: np.ndarray) -> np.ndarray:
 def decdec_select_topk(x, K: int, k: int, idx_out, xsel_out=None, stream=None):
     _check(lib().decdec_select_topk(_ptr(x), K, k, _ptr(idx_out), _ptr(xsel_out), _stream(stream)),
            "decdec_select_topk")
+
+
+def decdec_select_bucket(x, K: int, k_chunk: int, b0: float, b15: float, idx_out, xsel_out=None, stream=None):
+    _check(lib().decdec_select_bucket(_ptr(x), K, k_chunk, float(b0), float(b15), _ptr(idx_out), _ptr(xsel_out),
+                                      _stream(stream)), "decdec_select_bucket")
 
 
 def decdec_gemv(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales, k: int, y, ws: Workspace, stream=None):

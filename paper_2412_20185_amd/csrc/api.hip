@@ -356,6 +356,17 @@ int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k, int32_t* idx
     return DECDEC_OK;
 }
 
+int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, float b0, float b15,
+                         int32_t* idx_out_dev, void* xsel_f16_dev, void* stream) {
+    if (x_f16_dev == nullptr || K < 1024 || K % 1024 != 0 || k_chunk < 0 || k_chunk > 1024) return DECDEC_EINVAL;
+    if (!(b0 >= b15) || !(b15 >= 0.f)) return DECDEC_EINVAL;  // also rejects NaN
+    if (k_chunk == 0) return DECDEC_OK;
+    if (idx_out_dev == nullptr) return DECDEC_EINVAL;
+    DD_HIP(launch_select_bucket(x_f16_dev, K, k_chunk, b0, b15, idx_out_dev, xsel_f16_dev,
+                                static_cast<hipStream_t>(stream)));
+    return DECDEC_OK;
+}
+
 static int check_pinned_cached(decdec_ws* ws, const void* R_pinned) {
     for (int i = 0; i < ws->pinned_n; ++i)
         if (ws->pinned_ok[i] == R_pinned) return DECDEC_OK;

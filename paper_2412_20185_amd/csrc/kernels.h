@@ -67,6 +67,11 @@ int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out);
 hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream,
                               const KernelTimer* tm = nullptr);
 
+// select_bucket.hip ------------------------------------------------------
+// The paper's approximate Top-K: k_chunk channels per 1024-channel chunk (K a multiple of 1024).
+hipError_t launch_select_bucket(const void* x, int K, int k_chunk, float b0, float b15, int32_t* idx_out,
+                                void* xsel_out, hipStream_t stream, const KernelTimer* tm = nullptr);
+
 // fetch.hip --------------------------------------------------------------
 // cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic).
 int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split);

@@ -4,6 +4,8 @@
     python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and row split: us, GB/s
     python -m paper_2412_20185_amd.microbench ksweep   latency of a Llama-3-8B layer versus k (4-bit weights),
                                                        next to the knee model of the paper (Section 5.1)
+    python -m paper_2412_20185_amd.microbench select   exact radix select versus the paper's approximate bucket
+                                                       Top-K (Section 4.3): time per launch and recall
 
 Kernel durations are the dispatch timestamps the library records when
 profiling is switched on (decdec_ws_set_profiling), i.e. what a kernel trace
@@ -177,9 +179,50 @@ def ksweep(args):
     ws.close()
 
 
+def select(args):
+    """Stand-alone selection kernels on outlier-bearing activations (N(0,1), 0.5 % channels x U(10,50)):
+    wall time per launch over back-to-back launches (run under rocprofv3 --kernel-trace --stats for the
+    kernel durations) and recall of the approximate selector against the exact one (paper: about 80 % on
+    real activations, Section 5.2).  Boundaries b0 / b15 are calibrated on 32 other draws (Section 4.3)."""
+    import workloads
+    print(f"{'K':>6s} {'k_chunk':>7s} {'k':>5s} {'exact us':>9s} {'bucket us':>10s} {'recall':>7s} {'b0':>8s} {'b15':>7s}")
+    for K, which in ((4096, "attn_in"), (14336, "down_in")):
+        for k_chunk in (8, 20, 32, 64, 128):
+            k = k_chunk * K // 1024
+            cal = torch.from_numpy(np.stack([workloads.x_gauss_outliers(3, 0, which, 1000 + s, K) for s in range(32)]))
+            a = cal.float().abs()
+            b0 = float(a.max())
+            b15 = float(a.sort(dim=1).values[:, K - k].max())
+            xs = [torch.from_numpy(workloads.x_gauss_outliers(3, 0, which, s, K)).cuda() for s in range(16)]
+            ie = torch.empty(k, dtype=torch.int32, device="cuda")
+            ib = torch.empty(k, dtype=torch.int32, device="cuda")
+            v = torch.empty(k, dtype=torch.float16, device="cuda")
+            rec = []
+            for x in xs:
+                B.decdec_select_topk(x, K, k, ie, v)
+                B.decdec_select_bucket(x, K, k_chunk, b0, b15, ib, v)
+                torch.cuda.synchronize()
+                rec.append(np.intersect1d(ie.cpu().numpy(), ib.cpu().numpy()).size / k)
+            times = []
+            for fn in (lambda x: B.decdec_select_topk(x, K, k, ie, v),
+                       lambda x: B.decdec_select_bucket(x, K, k_chunk, b0, b15, ib, v)):
+                for i in range(20):
+                    fn(xs[i % 16])
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(args.reps * 5):
+                    fn(xs[i % 16])
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) * 1e3 / (args.reps * 5))
+            print(f"{K:6d} {k_chunk:7d} {k:5d} {times[0]:9.2f} {times[1]:10.2f} {np.mean(rec):7.3f} {b0:8.2f} {b15:7.3f}",
+                  flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=("gemv", "fetch", "ksweep"))
+    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select"))
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=12)
@@ -190,7 +233,7 @@ def main():
         print("needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep}[args.what](args)
+    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select}[args.what](args)
     return 0
 
 

@@ -55,6 +55,14 @@ def test_validation_without_gpu():
     assert L.decdec_select_topk(1, 1024, 3, None, None, None) == -1
     assert L.decdec_select_topk(1, 131072, 3, 1, None, None) == -1
     assert L.decdec_select_topk(1, 1024, 0, None, None, None) == 0                   # k = 0 enqueues nothing
+    # approximate selector: K not a multiple of 1024, k_chunk out of range, boundaries out of order or NaN
+    assert L.decdec_select_bucket(1, 1000, 3, C.c_float(2.0), C.c_float(1.0), 1, None, None) == -1
+    assert L.decdec_select_bucket(1, 2048, 1025, C.c_float(2.0), C.c_float(1.0), 1, None, None) == -1
+    assert L.decdec_select_bucket(1, 2048, 3, C.c_float(1.0), C.c_float(2.0), 1, None, None) == -1
+    assert L.decdec_select_bucket(1, 2048, 3, C.c_float(float("nan")), C.c_float(1.0), 1, None, None) == -1
+    assert L.decdec_select_bucket(1, 2048, 3, C.c_float(1.0), C.c_float(-1.0), 1, None, None) == -1
+    assert L.decdec_select_bucket(None, 2048, 3, C.c_float(2.0), C.c_float(1.0), 1, None, None) == -1
+    assert L.decdec_select_bucket(1, 2048, 0, C.c_float(2.0), C.c_float(1.0), None, None, None) == 0
     # packers
     codes = np.zeros((256, 128), np.uint8)
     codes[3, 5] = 8
