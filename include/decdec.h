@@ -105,8 +105,9 @@ int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, 
  * choice.  Affects later calls on this workspace. */
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
 
-/* How one compensated GEMV (k > 0) is laid out on the GPU.  The result is the
- * same bit for bit in every mode.
+/* How one compensated GEMV (k > 0) is laid out on the GPU.  Every mode adds the
+ * same terms in fp32; SERIAL and TWO_STREAMS give identical bits, FUSED splits K
+ * over larger workgroups, so its partial sums may round differently.
  *   FUSED (default): one kernel whose first workgroups do steps 1-3 (selection,
  *     zero-copy fetch, residual GEMV) and whose other workgroups do the base
  *     GEMV, then the accumulate kernel; everything on the caller's stream.
@@ -120,7 +121,7 @@ int decdec_ws_set_mode(decdec_ws* ws, int32_t mode);
 
 /* Where step 1 runs when decdec_gemv / decdec_gemv_multi select for themselves.
  * on = 0 (default): inside the residual kernel, every workgroup selecting for
- * itself (K <= 16384 and k <= 4096; larger problems use the selection kernel).
+ * itself (K <= 32768 and k <= 4096; larger problems use the selection kernel).
  * on = 1: always as a kernel of its own before the residual kernel.  The
  * selection is the same either way. */
 int decdec_ws_set_separate_select(decdec_ws* ws, int32_t on);

@@ -437,8 +437,10 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     // partial rows the other one contributes.
     long tiles = 0;
     for (int m = 0; m < count; ++m) tiles += sh.N[m] / kTileCols;
+    const bool fused = k > 0 && ws->mode == DECDEC_MODE_FUSED;
     int gpw = 1;
-    const int gslices = gemv_slices(tiles, sh.K / kGroup, ws->gemv_gpw, &gpw);
+    const int gslices =
+        gemv_slices(tiles, sh.K / kGroup, ws->gemv_gpw, fused ? kWavesPerBlock : kGemvAloneWaves, &gpw);
     const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, ws->fetch_split) : 0;
 
     FinalizeArgs fa{};
@@ -485,7 +487,7 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
                     if (pmask) *pmask |= 2;
                 }
             }
-            if (ws->mode == DECDEC_MODE_FUSED) {
+            if (fused) {
                 DD_HIP(launch_compensated_gemv(kind, d0->rfmt, sh, gop, fop, x, select_chunks, idx, xsel, k, ws->gpart,
                                                gslices, gpw, ws->cpart, cslices, fa, stream, tm[2]));
                 if (pmask) *pmask |= 4;

@@ -8,7 +8,7 @@ namespace decdec {
 namespace {
 
 template <int SELECT_NCH>
-__global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, const FinalizeArgs fa,
+__global__ __launch_bounds__(kBlockThreads) void fetch_fp16_kernel(const FetchJobs jobs, const FinalizeArgs fa,
                                                         const uint16_t* __restrict__ x, int32_t* idx_g,
                                                         uint16_t* xsel_g, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
@@ -16,7 +16,7 @@ __global__ __launch_bounds__(256) void fetch_fp16_kernel(const FetchJobs jobs, c
 }
 
 template <int SELECT_NCH>
-__global__ __launch_bounds__(256) void fetch_int4_kernel(const FetchJobs jobs, const FinalizeArgs fa,
+__global__ __launch_bounds__(kBlockThreads) void fetch_int4_kernel(const FetchJobs jobs, const FinalizeArgs fa,
                                                         const uint16_t* __restrict__ x, int32_t* idx_g,
                                                         uint16_t* xsel_g, int k, int K, int Ntot,
                                                         float* __restrict__ cpart, int wavecols, int slices) {
@@ -49,10 +49,11 @@ int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split) {
 }
 
 int fetch_select_chunks(int K, int k) {
-    // In-kernel selection: keys of a 256-thread workgroup stay in registers (at most 8 chunks of 8 per thread)
+    // In-kernel selection: the keys of a workgroup stay in registers (at most 8 chunks of 8 per thread)
     // and the selection must fit in LDS.
-    if (k < 1 || k > 4096 || K > 16384) return 0;
-    return K <= 4096 ? 2 : K <= 8192 ? 4 : 8;
+    constexpr int per_chunk_round = 8 * kBlockThreads;  // channels covered by one chunk per thread
+    if (k < 1 || k > 4096 || K > 8 * per_chunk_round) return 0;
+    return K <= per_chunk_round ? 1 : K <= 2 * per_chunk_round ? 2 : K <= 4 * per_chunk_round ? 4 : 8;
 }
 
 template <int NCH>
@@ -61,11 +62,11 @@ static hipError_t launch_fetch_nch(int rfmt, const FetchJobs& jobs, const Finali
                                    int slices, dim3 grid, hipStream_t stream, const KernelTimer* tm) {
     const unsigned lds = NCH > 0 ? (unsigned)(((size_t)k * 6 + 15) / 16 * 16) : 0u;
     if (rfmt == 0) {
-        return launch_kernel(tm, fetch_fp16_kernel<NCH>, grid, dim3(256), lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
-                             cpart, wc, slices);
+        return launch_kernel(tm, fetch_fp16_kernel<NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
+                             Ntot, cpart, wc, slices);
     }
-    return launch_kernel(tm, fetch_int4_kernel<NCH>, grid, dim3(256), lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
-                         cpart, wc, slices);
+    return launch_kernel(tm, fetch_int4_kernel<NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
+                         Ntot, cpart, wc, slices);
 }
 
 // select_chunks > 0: the kernel selects for itself from x (and writes the selection to idx / xsel);
@@ -85,12 +86,13 @@ hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op,
         jobs.wc_end[m] = wc;
     }
     const int tasks = wc * slices;
-    const dim3 grid((unsigned)((tasks + 3) / 4));
+    const dim3 grid((unsigned)((tasks + kWavesPerBlock - 1) / kWavesPerBlock));
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* xs = static_cast<uint16_t*>(xsel);
     const int Ntot = sh.col0[sh.n];
     switch (select_chunks) {
         case 0: return launch_fetch_nch<0>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
+        case 1: return launch_fetch_nch<1>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
         case 2: return launch_fetch_nch<2>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
         case 4: return launch_fetch_nch<4>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
         case 8: return launch_fetch_nch<8>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);

@@ -56,7 +56,7 @@ struct WaveTask {
 // of the concatenated matrices.
 __device__ __forceinline__ WaveTask wave_task(const FetchJobs& jobs, int wavecols, int slices, int bid) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int task = bid * 4 + wave;
+    const int task = bid * kWavesPerBlock + wave;
     WaveTask t;
     t.valid = task < wavecols * slices;
     t.rs = task / wavecols;
@@ -84,10 +84,10 @@ __device__ __forceinline__ Selection obtain_selection(const uint16_t* __restrict
         __shared__ SelectShared sh;
         int32_t* idx_l = reinterpret_cast<int32_t*>(s_sel_raw);
         uint16_t* xs_l = reinterpret_cast<uint16_t*>(idx_l + k);
-        block_select_topk<256, SELECT_NCH>(x, K, k, sh, idx_l, xs_l);
+        block_select_topk<kBlockThreads, SELECT_NCH>(x, K, k, sh, idx_l, xs_l);
         __syncthreads();
         if (bid == 0) {
-            for (int i = threadIdx.x; i < k; i += 256) {
+            for (int i = threadIdx.x; i < k; i += kBlockThreads) {
                 idx_g[i] = idx_l[i];
                 xsel_g[i] = xs_l[i];
             }

@@ -22,7 +22,7 @@ namespace decdec {
 namespace {
 
 template <int KIND, int RFMT, int SELECT_NCH>
-__global__ __launch_bounds__(256) void compensated_gemv_kernel(
+__global__ __launch_bounds__(kBlockThreads) void compensated_gemv_kernel(
     const GemvJobs gjobs, const FetchJobs fjobs, const FinalizeArgs fa, const uint16_t* __restrict__ x,
     int32_t* idx_g, uint16_t* xsel_g, int k, int K, int Ntot, float* __restrict__ gpart, float* __restrict__ cpart,
     int G, int gslices, int gpw, int wavecols, int cslices, int nfetch) {
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void compensated_gemv_kernel(
             fetch_int4_block<SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
         }
     } else {
-        gemv_block<KIND>(gjobs, fa, reinterpret_cast<const uint32_t*>(x), gpart, Ntot, G, gslices, gpw, bid - nfetch);
+        gemv_block<KIND, kWavesPerBlock>(gjobs, fa, reinterpret_cast<const uint32_t*>(x), gpart, Ntot, G, gslices, gpw, bid - nfetch);
     }
 }
 
@@ -43,10 +43,13 @@ hipError_t launch_nch(int nch, const KernelTimer* tm, dim3 grid, unsigned lds, h
                       const GemvJobs& gj, const FetchJobs& fj, const FinalizeArgs& fa, const uint16_t* x, int32_t* idx,
                       uint16_t* xs, int k, int K, int Ntot, float* gpart, float* cpart, int G, int gslices, int gpw,
                       int wc, int cslices, int nfetch) {
-    const dim3 block(256);
+    const dim3 block(kBlockThreads);
     switch (nch) {
         case 0:
             return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 0>, grid, block, lds, stream, gj, fj, fa, x, idx,
+                                 xs, k, K, Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
+        case 1:
+            return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 1>, grid, block, lds, stream, gj, fj, fa, x, idx,
                                  xs, k, K, Ntot, gpart, cpart, G, gslices, gpw, wc, cslices, nfetch);
         case 2:
             return launch_kernel(tm, compensated_gemv_kernel<KIND, RFMT, 2>, grid, block, lds, stream, gj, fj, fa, x, idx,
@@ -92,7 +95,7 @@ hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, con
         wc += (sh.N[m] + cpw - 1) / cpw;
         fj.wc_end[m] = wc;
     }
-    const int nfetch = (wc * cslices + 3) / 4;
+    const int nfetch = (wc * cslices + kWavesPerBlock - 1) / kWavesPerBlock;
     const dim3 grid((unsigned)(nfetch + tiles * gslices));
     const unsigned lds = select_chunks > 0 ? (unsigned)(((size_t)k * 6 + 15) / 16 * 16) : 0u;
     const uint16_t* xp = static_cast<const uint16_t*>(x);

@@ -8,26 +8,26 @@ namespace decdec {
 namespace {
 
 template <int KIND>
-__global__ __launch_bounds__(256) void gemv_kernel(const GemvJobs jobs, const FinalizeArgs fa,
+__global__ __launch_bounds__(kGemvAloneWaves * 64) void gemv_kernel(const GemvJobs jobs, const FinalizeArgs fa,
                                                   const uint32_t* __restrict__ x32, float* __restrict__ part,
                                                   int Ntot, int G, int slices, int gpw) {
-    gemv_block<KIND>(jobs, fa, x32, part, Ntot, G, slices, gpw, (int)blockIdx.x);
+    gemv_block<KIND, kGemvAloneWaves>(jobs, fa, x32, part, Ntot, G, slices, gpw, (int)blockIdx.x);
 }
 
 }  // namespace
 
-int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out) {
+int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gpw_out) {
     // One group per wavefront while that keeps the grid within what the chip
     // holds at once (256 CUs x 32 waves): the whole matrix is then requested in
     // one go.  Larger problems give every wavefront several groups.
     const long units = tiles * G;
     int gpw = gpw_request > 0 ? gpw_request : (int)((units + 8191) / 8192);
     if (gpw < 1) gpw = 1;
-    int per_block = gpw * kWavesPerBlock;
+    int per_block = gpw * waves_per_block;
     int slices = (G + per_block - 1) / per_block;
     while (slices > kMaxGemvSlices) {
         ++gpw;
-        per_block = gpw * kWavesPerBlock;
+        per_block = gpw * waves_per_block;
         slices = (G + per_block - 1) / per_block;
     }
     *gpw_out = gpw;
@@ -49,7 +49,7 @@ hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, c
         tiles += sh.N[m] / kTileCols;
         jobs.tile_end[m] = tiles;
     }
-    const dim3 grid((unsigned)(tiles * slices)), block(256);
+    const dim3 grid((unsigned)(tiles * slices)), block(kGemvAloneWaves * 64);
     const uint32_t* x32 = static_cast<const uint32_t*>(x);
     const int Ntot = sh.col0[sh.n];
     switch (kind) {

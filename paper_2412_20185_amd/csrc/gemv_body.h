@@ -152,7 +152,6 @@ __device__ __forceinline__ float group_dot_lut3(const uint4 (&q)[3], const LutTa
     return acc0 + acc1;
 }
 
-constexpr int kWavesPerBlock = 4;
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -214,18 +213,18 @@ struct GemvJobs {
     int n;
 };
 
-// Work of workgroup `bid` out of (total tiles) * slices workgroups of 256 threads; workgroup (nt, ks)
+// Work of workgroup `bid` out of (total tiles) * slices workgroups of WPB wavefronts; workgroup (nt, ks)
 // covers column tile nt (of whichever matrix it falls in) and groups
-// [ks*4*gpw, (ks+1)*4*gpw), wave w of it the gpw groups starting at
-// (ks*4 + w)*gpw.  part is fp32 [slices][Ntot].  The loads of the next tile
+// [ks*WPB*gpw, (ks+1)*WPB*gpw), wave w of it the gpw groups starting at
+// (ks*WPB + w)*gpw.  part is fp32 [slices][Ntot].  The loads of the next tile
 // are issued before the current one is consumed.
-template <int KIND>
+template <int KIND, int WPB>
 __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeArgs& fa,
                                            const uint32_t* __restrict__ x32, float* __restrict__ part, int Ntot,
                                            int G, int slices, int gpw, int bid) {
     constexpr int P = words_per_lane(KIND) / 4;  // 16-byte pieces per lane per tile
     constexpr int kTileStride = P * kTileCols;   // uint4 per tile
-    __shared__ float red[kWavesPerBlock][kTileCols];
+    __shared__ float red[WPB][kTileCols];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -240,7 +239,7 @@ __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeA
     const uint16_t* __restrict__ scales = jobs.scales[m];
     const uint16_t* __restrict__ zeros_or_lut = jobs.zeros_or_lut[m];
 
-    int g = (ks * kWavesPerBlock + wave) * gpw;
+    int g = (ks * WPB + wave) * gpw;
     const int g_end = min(g + gpw, G);
 
     LutTables T{};
@@ -267,7 +266,7 @@ __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeA
     if (wave == 0) {
         float v = red[0][lane];
 #pragma unroll
-        for (int w = 1; w < kWavesPerBlock; ++w) v += red[w][lane];
+        for (int w = 1; w < WPB; ++w) v += red[w][lane];
         store_partial(part + (size_t)ks * Ntot + jobs.col0[m] + n, v, fa.counters != nullptr);
         if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, m, nt, 1, lane);
     }

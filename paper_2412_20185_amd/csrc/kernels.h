@@ -9,6 +9,12 @@
 
 namespace decdec {
 
+// Workgroup size of the base-GEMV, residual and fused kernels (one wavefront = one unit of work in all of them).
+constexpr int kBlockThreads = 512;
+constexpr int kWavesPerBlock = kBlockThreads / 64;
+// The base GEMV on its own (k = 0) runs fastest with smaller workgroups.
+constexpr int kGemvAloneWaves = 4;
+
 constexpr int kMaxGemvSlices = 64;   // fp32 partial rows the base GEMV may write
 constexpr int kMaxFetchSlices = 64;  // fp32 partial rows the residual kernel may write
 constexpr int kSelectThreads = 1024;
@@ -61,7 +67,8 @@ struct FinalizeArgs;
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
                        int slices, int gpw, const FinalizeArgs& fa, hipStream_t stream,
                        const KernelTimer* tm = nullptr);
-int gemv_slices(long tiles, int G, int gpw_request, int* gpw_out);
+// waves_per_block: kGemvAloneWaves for launch_gemv, kWavesPerBlock inside the fused kernel.
+int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gpw_out);
 
 // select.hip -------------------------------------------------------------
 hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream,
