@@ -40,13 +40,15 @@ CFG = 2                     # BASELINE config index used for seeding (configs[1]
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=120)
-    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--layers", type=int, default=6, help="distinct layers rotated over (HBM-cold weights)")
     ap.add_argument("--xpool", type=int, default=32, help="distinct activation draws rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fetch-split", type=int, default=0)
-    ap.add_argument("--graph", type=int, default=1, help="1: replay each distinct step as a captured HIP graph")
+    ap.add_argument("--graph", type=int, default=1, help="1: replay the steps as captured HIP graphs")
+    ap.add_argument("--graph-steps", type=int, default=8,
+                    help="consecutive steps captured into one graph (a decoder captures all its layers at once)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--grouping", choices=("grouped", "separate"), default="grouped",
@@ -109,48 +111,42 @@ def main() -> int:
 
     graphs = {}
     cap_stream = torch.cuda.Stream() if args.graph else None
+    gs = max(1, args.graph_steps) if args.graph else 1
 
-    def run_step(i: int, compensate: bool):
-        """One step, eagerly or as a replay of its captured graph."""
-        if not args.graph:
-            step(i, compensate)
-            return
+    def run_steps(i0: int, n: int, compensate: bool):
+        """Steps i0 .. i0+n-1, eagerly or as replays of captured graphs of `gs` consecutive steps each
+        (a tail shorter than gs runs eagerly)."""
         import math
-        key = (i % math.lcm(args.layers, args.xpool), compensate)
-        g = graphs.get(key)
-        if g is None:
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=cap_stream):
+        i = i0
+        while i < i0 + n:
+            if args.graph and i % gs == 0 and i + gs <= i0 + n:
+                key = (i % math.lcm(args.layers, args.xpool, gs), compensate)
+                g = graphs.get(key)
+                if g is None:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=cap_stream):
+                        for j in range(i, i + gs):
+                            step(j, compensate)
+                    graphs[key] = g
+                g.replay()
+                i += gs
+            else:
                 step(i, compensate)
-            graphs[key] = g
-        g.replay()
+                i += 1
 
     def timed(n: int, compensate: bool) -> float:
         if args.graph:
-            for i in range(n):          # capture outside the timed region
-                run_step(i, compensate)
+            run_steps(0, n, compensate)          # capture outside the timed region
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(n):
-            run_step(i, compensate)
+        run_steps(0, n, compensate)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
-    if args.pmc_calibrate:
-        # a plain elementwise kernel that reads 256 MiB and writes 256 MiB, 4 times
-        a = torch.ones(64 << 20, dtype=torch.int32, device="cuda")
-        b = torch.empty_like(a)
-        for _ in range(4):
-            torch.add(a, 1, out=b)
-        torch.cuda.synchronize()
-        del a, b
-
     # ------------------------------------------------------------ timed region
-    for i in range(args.warmup):
-        run_step(i, True)
+    run_steps(0, args.warmup, True)
     ms_step = timed(args.steps, True)
-    for i in range(args.warmup):
-        run_step(i, False)
+    run_steps(0, args.warmup, False)
     ms_base = timed(args.steps, False)
 
     # --------------------------------- per-kernel durations over the same steps
@@ -225,7 +221,7 @@ def main() -> int:
         "select_avg_us": round(s_ms * 1e3 / max(s_n, 1), 3),
         "accumulate_avg_us": round(prof["accumulate"][0] * 1e3 / max(prof["accumulate"][1], 1), 3),
         "setup_s": round(setup_s, 1),
-        "launch": "hip-graph replay" if args.graph else "eager",
+        "launch": f"hip-graph replay, {gs} steps per graph" if args.graph else "eager",
         "grouping": args.grouping,
         "calls_per_step": n_calls,
     }

@@ -261,3 +261,16 @@ def test_all_layouts_of_the_work_give_the_same_bits(ws, wfmt, bits, rfmt):
             assert np.array_equal(outs[1].view(np.uint16), outs[2].view(np.uint16))
     finally:
         ws.set_mode(dd.MODE_FUSED)
+
+
+@pytest.mark.parametrize("K,N,k", [(40960, 128, 100), (8192, 256, 5000), (65536, 64, 1311)])
+def test_large_problems_fall_back_to_the_selection_kernel(K, N, k):
+    """Beyond 32768 channels or 4096 selected channels the selection does not fit
+    the fetch workgroups' registers / LDS and runs as a kernel of its own."""
+    ws = dd.Workspace(65536, 256, 8192)
+    p = Problem(workloads.weights(67, 0, 0, K, N), 4)
+    x = workloads.x_student_t(67, 0, 0, 0, K, outlier_frac=0.005)
+    y_ref, sc = p.reference(x, k)
+    y, idx, _ = p.run(x, k, ws)
+    assert_parity(y, y_ref, idx, sc, what=f"fallback select {K}x{N} k={k}")
+    ws.close()
