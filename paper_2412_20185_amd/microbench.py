@@ -6,6 +6,8 @@
                                                        next to the knee model of the paper (Section 5.1)
     python -m paper_2412_20185_amd.microbench select   exact radix select versus the paper's approximate bucket
                                                        Top-K (Section 4.3): time per launch and recall
+    python -m paper_2412_20185_amd.microbench tune     the paper's parameter tuner (Section 4.4) on this GPU:
+                                                       fetch workgroups and k_chunk per layer type for target slowdowns
 
 Kernel durations are the dispatch timestamps the library records when
 profiling is switched on (decdec_ws_set_profiling), i.e. what a kernel trace
@@ -220,9 +222,65 @@ def select(args):
                   flush=True)
 
 
+def tune(args):
+    """Section 4.4 on a Llama-3-8B-shaped layer (3-bit weights, fp16 host residuals): for each target slowdown
+    over the uncompensated layer, the row split of the fetch (this library's counterpart of n_tb: fetch
+    workgroups = column segments x row split / 8) and k_chunk per layer type.  measure() = wall time of one
+    layer (4 calls) replayed as a captured graph."""
+    import time
+    import workloads
+    from .layer import LinearGroup, UniformLinear
+    from . import tuner as T
+    shapes = workloads.LLAMA3_8B_LAYER
+    lins = {name: UniformLinear(workloads.weights(2, 0, name, K, N), 3) for name, K, N, _ in shapes}
+    ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
+    order = [("qkv", "attn_in", ["q", "k", "v"]), ("o", "o_in", ["o"]), ("gu", "mlp_in", ["gate", "up"]),
+             ("d", "down_in", ["down"])]
+    groups = {t: LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for t, _, names in order}
+    Kof = {t: lins[names[0]].K for t, _, names in order}
+    xin = {w: torch.from_numpy(workloads.x_gauss_outliers(2, 0, w, 0, K)).cuda()
+           for w, K in {(w, lins[names[0]].K) for _, w, names in order}}
+    ws = B.Workspace(14336, 28672, 4096)
+    stream = torch.cuda.Stream()
+    splits = (1, 2, 4, 8, 16, 32)
+    types = [T.LayerType(t, Kof[t], sum(lins[n].N for n in names), candidates=splits) for t, _, names in order]
+    cache = {}
+
+    def measure(cfg):
+        key = tuple(sorted(cfg.items()))
+        if key in cache:
+            return cache[key]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for t, w, names in order:
+                split, kc = cfg[t]
+                ws.set_fetch_split(split)
+                groups[t].gemv(xin[w], workloads.k_for_kchunk(Kof[t], kc), ws)
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.reps):
+            g.replay()
+        torch.cuda.synchronize()
+        cache[key] = (time.perf_counter() - t0) * 1e6 / args.reps
+        return cache[key]
+
+    print("target   row-split cap  split (qkv,o,gu,d)   k_chunk (qkv,o,gu,d)   baseline us  tuned us  slowdown  frozen")
+    for target in (0.025, 0.05, 0.1, 0.2, 0.5, 1.0, 2.0, 4.0):
+        r = T.tune(types, measure, target, ntb_max_limit=32, k_chunk_limit=128)
+        names = [t for t, _, _ in order]
+        print(f"{target * 100:6.1f}%  {r.ntb_max:13d}  {str(tuple(r.ntb[n] for n in names)):19s}  "
+              f"{str(tuple(r.k_chunk[n] for n in names)):21s}  {r.baseline:11.1f}  {r.time:8.1f}  {r.slowdown * 100:7.1f}%  "
+              f"{','.join(r.frozen) or '-'}", flush=True)
+    print(f"{len(cache)} configurations measured")
+    ws.set_fetch_split(0)
+    ws.close()
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select"))
+    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select", "tune"))
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=12)
@@ -233,7 +291,7 @@ def main():
         print("needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select}[args.what](args)
+    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select, "tune": tune}[args.what](args)
     return 0
 
 
