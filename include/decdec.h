@@ -69,8 +69,17 @@ typedef enum { DECDEC_W_UNIFORM_G128 = 0, DECDEC_W_LUT_COL8 = 1 } decdec_wfmt;
  *                  N/2 contiguous bytes; byte j holds column 2j in its low
  *                  nibble and column 2j+1 in its high nibble, each a 4-bit
  *                  two's-complement integer.
+ *   INT2_SYM_COL / INT8_SYM_COL: the same with 2-bit codes in [-1, 1] (four per
+ *                  byte, column 4j+i in bits 2i..2i+1) or 8-bit codes in
+ *                  [-127, 127] (one per byte): the variants of the paper's
+ *                  residual bit-width study (Table 2).
  */
-typedef enum { DECDEC_R_FP16 = 0, DECDEC_R_INT4_SYM_COL = 1 } decdec_rfmt;
+typedef enum {
+    DECDEC_R_FP16 = 0,
+    DECDEC_R_INT4_SYM_COL = 1,
+    DECDEC_R_INT2_SYM_COL = 2,
+    DECDEC_R_INT8_SYM_COL = 3
+} decdec_rfmt;
 
 typedef struct {
     int32_t K;      /* input channels  (d_in),  multiple of 128 */
@@ -164,6 +173,9 @@ int decdec_unpack_weights(const decdec_desc* d, const void* packed, uint8_t* cod
 /* codes: host int8 [K][N] in [-7,7] -> out: host bytes [K][N/2] in the
  * INT4_SYM_COL row format above. */
 int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint8_t* out);
+/* The same for bits in {2, 4, 8}: codes in [-(2^(bits-1) - 1), 2^(bits-1) - 1],
+ * out: host bytes [K][N * bits / 8]; N a multiple of 128 / bits. */
+int decdec_pack_residual_int(int32_t K, int32_t N, int32_t bits, const int8_t* codes_KN, uint8_t* out);
 
 /* ------------------------------------------------------------ hot path */
 
@@ -203,8 +215,8 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  *   Wq_dev         dev, packed by decdec_pack_weights (or decdec_quantize_uniform)
  *   scales_f16_dev dev fp16 [K/128][N]           (UNIFORM; ignored for LUT)
  *   zeros_or_lut   dev fp16 [K/128][N] zero points (UNIFORM) or fp16 [N][8] (LUT)
- *   R_pinned       pinned fp16 [K][N] or int4 bytes [K][N/2]; may be NULL if k == 0
- *   R_scales_f16_dev dev fp16 [N] (INT4_SYM_COL only, else NULL)
+ *   R_pinned       pinned fp16 [K][N] or integer codes [K][N*bits/8]; may be NULL if k == 0
+ *   R_scales_f16_dev dev fp16 [N] (integer residual formats only, else NULL)
  *   k              salient channels, 0 <= k <= min(K, maxk of ws)
  *   y_f16_dev      dev fp16 [N] out
  * By default the base GEMV and steps 1-3 run side by side inside one kernel on

@@ -24,7 +24,7 @@ third-party step and are pinned only as to their stated definition.
 """
 from .quantize import (  # noqa: F401
     GROUP, quantize_uniform, dequantize_uniform, quantize_lut, dequantize_lut,
-    residual_fp16, quantize_residual_int4, dequantize_residual_int4,
+    residual_fp16, quantize_residual_sym, quantize_residual_int4, dequantize_residual_int4,
 )
 from .select import topk_abs, magnitude_keys  # noqa: F401
 from .bucket_select import (  # noqa: F401

@@ -108,33 +108,45 @@ def residual_fp16(W, W_hat) -> np.ndarray:
 DEFAULT_ALPHAS = np.round(np.arange(30, 101) / 100.0, 2)
 
 
-def quantize_residual_int4(R, alphas=DEFAULT_ALPHAS):
-    """4-bit symmetric residual quantiser, one scale per output column
-    (Section 4.2): Q_i(r) = clip(round_to_int(r / S_i), -7, 7), S_i found by
-    grid search for the least squared error of column i.
+def quantize_residual_sym(R, bits, alphas=DEFAULT_ALPHAS):
+    """b-bit symmetric residual quantiser, one scale per output column:
+    Q_i(r) = clip(round_to_int(r / S_i), -qmax, qmax) with
+    qmax = 2^(b-1) - 1, S_i found by grid search for the least squared error
+    of column i.  b = 4 (qmax 7) is the quantiser of Section 4.2; b = 2
+    (codes -1, 0, 1) and b = 8 (qmax 127) are the other integer widths of the
+    residual bit-width study (Table 2).
 
     Reading of what the paper leaves open: round_to_int is round-half-even;
-    the grid is S = fp16(alpha * max|r| / 7) for alpha in `alphas`
+    the grid is S = fp16(alpha * max|r| / qmax) for alpha in `alphas`
     (0.30 ... 1.00 step 0.01); ties keep the larger alpha; an all-zero column
-    gets S = 1.
+    gets S = 1; the 2- and 8-bit quantisers (not written out in the paper)
+    are the same formula with their own qmax.
     """
+    if bits not in (2, 4, 8):
+        raise ValueError("bits must be 2, 4 or 8")
+    qmax = float(2 ** (bits - 1) - 1)
     R = np.asarray(R, dtype=np.float64)
     K, N = R.shape
     m = np.abs(R).max(axis=0)
     best_err = np.full(N, np.inf)
     best_S = np.ones(N, dtype=np.float16)
     for a in alphas:
-        S = (a * m / 7.0).astype(np.float16)
+        S = (a * m / qmax).astype(np.float16)
         S[S == 0] = np.float16(1.0)
         Sd = S.astype(np.float64)
-        q = np.clip(np.rint(R / Sd), -7, 7)
+        q = np.clip(np.rint(R / Sd), -qmax, qmax)
         err = ((R - Sd * q) ** 2).sum(axis=0)
         take = err <= best_err
         best_err = np.where(take, err, best_err)
         best_S = np.where(take, S, best_S)
     Sd = best_S.astype(np.float64)
-    q = np.clip(np.rint(R / Sd), -7, 7).astype(np.int8)
+    q = np.clip(np.rint(R / Sd), -qmax, qmax).astype(np.int8)
     return q, best_S
+
+
+def quantize_residual_int4(R, alphas=DEFAULT_ALPHAS):
+    """The 4-bit residual quantiser of Section 4.2 (codes in [-7, 7])."""
+    return quantize_residual_sym(R, 4, alphas)
 
 
 def dequantize_residual_int4(Rq, Rs) -> np.ndarray:

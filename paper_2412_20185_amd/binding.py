@@ -18,13 +18,14 @@ lib_path = os.path.join(_HERE, "libdecdec.so")
 
 W_UNIFORM_G128, W_LUT_COL8 = 0, 1
 MODE_FUSED, MODE_SERIAL, MODE_TWO_STREAMS = 0, 1, 2
-R_FP16, R_INT4_SYM_COL = 0, 1
+R_FP16, R_INT4_SYM_COL, R_INT2_SYM_COL, R_INT8_SYM_COL = 0, 1, 2, 3
+R_FMT_OF_BITS = {16: R_FP16, 4: R_INT4_SYM_COL, 2: R_INT2_SYM_COL, 8: R_INT8_SYM_COL}
 
 EXPORTED_SYMBOLS = (
     "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
     "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
-    "decdec_pack_residual_int4", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
+    "decdec_pack_residual_int4", "decdec_pack_residual_int", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
     "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
 )
 
@@ -86,6 +87,7 @@ def lib() -> C.CDLL:
     L.decdec_pack_weights.argtypes = [dp, vp, vp]
     L.decdec_unpack_weights.argtypes = [dp, vp, vp]
     L.decdec_pack_residual_int4.argtypes = [i32, i32, vp, vp]
+    L.decdec_pack_residual_int.argtypes = [i32, i32, i32, vp, vp]
     L.decdec_select_topk.argtypes = [vp, i32, i32, vp, vp, vp]
     L.decdec_select_bucket.argtypes = [vp, i32, i32, C.c_float, C.c_float, vp, vp, vp]
     L.decdec_gemv.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
@@ -220,6 +222,14 @@ def decdec_pack_residual_int4(codes_KN: np.ndarray) -> np.ndarray:
     K, N = codes.shape
     out = np.empty((K, N // 2), dtype=np.uint8)
     _check(lib().decdec_pack_residual_int4(K, N, codes.ctypes.data, out.ctypes.data), "decdec_pack_residual_int4")
+    return out
+
+
+def decdec_pack_residual_int(codes_KN: np.ndarray, bits: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes_KN, dtype=np.int8)
+    K, N = codes.shape
+    out = np.empty((K, N * bits // 8), dtype=np.uint8)
+    _check(lib().decdec_pack_residual_int(K, N, bits, codes.ctypes.data, out.ctypes.data), "decdec_pack_residual_int")
     return out
 
 

@@ -42,7 +42,7 @@ int check_desc(const decdec_desc* d) {
     if (d == nullptr) return DECDEC_EINVAL;
     if (d->K <= 0 || d->N <= 0 || d->K % kGroup != 0 || d->N % kTileCols != 0) return DECDEC_EINVAL;
     if (d->wfmt != DECDEC_W_UNIFORM_G128 && d->wfmt != DECDEC_W_LUT_COL8) return DECDEC_EINVAL;
-    if (d->rfmt != DECDEC_R_FP16 && d->rfmt != DECDEC_R_INT4_SYM_COL) return DECDEC_EINVAL;
+    if (d->rfmt < DECDEC_R_FP16 || d->rfmt > DECDEC_R_INT8_SYM_COL) return DECDEC_EINVAL;
     if (d->wbits != 3 && d->wbits != 4) return DECDEC_EINVAL;
     if (pack_kind(d) < 0) return DECDEC_EUNSUPPORTED;
     return DECDEC_OK;
@@ -333,16 +333,27 @@ int decdec_unpack_weights(const decdec_desc* d, const void* packed, uint8_t* cod
     return DECDEC_OK;
 }
 
-int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint8_t* out) {
-    if (K <= 0 || N <= 0 || N % 32 != 0 || codes_KN == nullptr || out == nullptr) return DECDEC_EINVAL;
+int decdec_pack_residual_int(int32_t K, int32_t N, int32_t bits, const int8_t* codes_KN, uint8_t* out) {
+    if (bits != 2 && bits != 4 && bits != 8) return DECDEC_EUNSUPPORTED;
+    const int per_byte = 8 / bits, qmax = (1 << (bits - 1)) - 1;
+    if (K <= 0 || N <= 0 || N % (128 / bits) != 0 || codes_KN == nullptr || out == nullptr) return DECDEC_EINVAL;
+    const size_t row_bytes = (size_t)N / per_byte;
     for (size_t r = 0; r < (size_t)K; ++r) {
-        for (size_t j = 0; j < (size_t)N / 2; ++j) {
-            const int a = codes_KN[r * N + 2 * j], b = codes_KN[r * N + 2 * j + 1];
-            if (a < -7 || a > 7 || b < -7 || b > 7) return DECDEC_EINVAL;
-            out[r * (N / 2) + j] = (uint8_t)((a & 0xF) | ((b & 0xF) << 4));
+        for (size_t j = 0; j < row_bytes; ++j) {
+            unsigned byte = 0;
+            for (int i = 0; i < per_byte; ++i) {
+                const int q = codes_KN[r * N + j * per_byte + i];
+                if (q < -qmax || q > qmax) return DECDEC_EINVAL;
+                byte |= ((unsigned)q & ((1u << bits) - 1u)) << (bits * i);
+            }
+            out[r * row_bytes + j] = (uint8_t)byte;
         }
     }
     return DECDEC_OK;
+}
+
+int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint8_t* out) {
+    return decdec_pack_residual_int(K, N, 4, codes_KN, out);
 }
 
 // ---------------------------------------------------------------- hot path
@@ -413,7 +424,7 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
         if (have_idx && (idx_in == nullptr || xsel_in == nullptr)) return DECDEC_EINVAL;
         for (int m = 0; m < count; ++m) {
             if (lin[m].R_pinned == nullptr) return DECDEC_EINVAL;
-            if (d0->rfmt == DECDEC_R_INT4_SYM_COL && lin[m].R_scales_f16_dev == nullptr) return DECDEC_EINVAL;
+            if (d0->rfmt != DECDEC_R_FP16 && lin[m].R_scales_f16_dev == nullptr) return DECDEC_EINVAL;
             const int prc = check_pinned_cached(ws, lin[m].R_pinned);
             if (prc != DECDEC_OK) return prc;
         }
@@ -437,7 +448,9 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     // partial rows the other one contributes.
     long tiles = 0;
     for (int m = 0; m < count; ++m) tiles += sh.N[m] / kTileCols;
-    const bool fused = k > 0 && ws->mode == DECDEC_MODE_FUSED;
+    // The one-grid kernel is built for fp16 and 4-bit residuals; the other formats take the separate kernels.
+    const bool fused = k > 0 && ws->mode == DECDEC_MODE_FUSED &&
+                       (d0->rfmt == DECDEC_R_FP16 || d0->rfmt == DECDEC_R_INT4_SYM_COL);
     int gpw = 1;
     const int gslices =
         gemv_slices(tiles, sh.K / kGroup, ws->gemv_gpw, fused ? kWavesPerBlock : kGemvAloneWaves, &gpw);

@@ -15,15 +15,17 @@ __global__ __launch_bounds__(kBlockThreads) void fetch_fp16_kernel(const FetchJo
     fetch_fp16_block<SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices, (int)blockIdx.x);
 }
 
-template <int SELECT_NCH>
-__global__ __launch_bounds__(kBlockThreads) void fetch_int4_kernel(const FetchJobs jobs, const FinalizeArgs fa,
-                                                        const uint16_t* __restrict__ x, int32_t* idx_g,
-                                                        uint16_t* xsel_g, int k, int K, int Ntot,
-                                                        float* __restrict__ cpart, int wavecols, int slices) {
-    fetch_int4_block<SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices, (int)blockIdx.x);
+template <int BITS, int SELECT_NCH>
+__global__ __launch_bounds__(kBlockThreads) void fetch_int_kernel(const FetchJobs jobs, const FinalizeArgs fa,
+                                                                 const uint16_t* __restrict__ x, int32_t* idx_g,
+                                                                 uint16_t* xsel_g, int k, int K, int Ntot,
+                                                                 float* __restrict__ cpart, int wavecols,
+                                                                 int slices) {
+    fetch_int_block<BITS, SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices,
+                                      (int)blockIdx.x);
 }
 
-inline int cols_per_wave(int rfmt) { return rfmt == 0 ? 512 : 2048; }
+inline int cols_per_wave(int rfmt) { return fetch_cols_per_wave(rfmt); }
 
 inline int total_wavecols(int rfmt, const MultiShape& sh) {
     int wc = 0;
@@ -65,7 +67,15 @@ static hipError_t launch_fetch_nch(int rfmt, const FetchJobs& jobs, const Finali
         return launch_kernel(tm, fetch_fp16_kernel<NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
                              Ntot, cpart, wc, slices);
     }
-    return launch_kernel(tm, fetch_int4_kernel<NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
+    if (rfmt == 1) {
+        return launch_kernel(tm, fetch_int_kernel<4, NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k,
+                             K, Ntot, cpart, wc, slices);
+    }
+    if (rfmt == 2) {
+        return launch_kernel(tm, fetch_int_kernel<2, NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k,
+                             K, Ntot, cpart, wc, slices);
+    }
+    return launch_kernel(tm, fetch_int_kernel<8, NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
                          Ntot, cpart, wc, slices);
 }
 

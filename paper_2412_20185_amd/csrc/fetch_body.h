@@ -157,13 +157,17 @@ __device__ __forceinline__ void fetch_fp16_block(const FetchJobs& jobs, const Fi
     if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, t.m, t.wc * 8, min(8, N / 64 - t.wc * 8), lane);
 }
 
-// 4-bit residuals (Section 4.2): a 16-byte piece holds 32 columns; a wave
-// covers 2048 columns.  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
-template <int SELECT_NCH>
-__device__ __forceinline__ void fetch_int4_block(const FetchJobs& jobs, const FinalizeArgs& fa,
-                                                const uint16_t* __restrict__ x, int32_t* idx_g, uint16_t* xsel_g,
-                                                int k, int K, int Ntot, float* __restrict__ cpart, int wavecols,
-                                                int slices, int bid) {
+// Integer residuals (Section 4.2: 4-bit symmetric with one scale per output
+// column; 2- and 8-bit are the variants of the paper's bit-width study, Table
+// 2): a 16-byte piece holds CPL = 128/BITS columns; a wave covers 64*CPL
+// columns.  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
+template <int BITS, int SELECT_NCH>
+__device__ __forceinline__ void fetch_int_block(const FetchJobs& jobs, const FinalizeArgs& fa,
+                                               const uint16_t* __restrict__ x, int32_t* idx_g, uint16_t* xsel_g,
+                                               int k, int K, int Ntot, float* __restrict__ cpart, int wavecols,
+                                               int slices, int bid) {
+    constexpr int CPL = 128 / BITS;  // columns per lane
+    constexpr int CPW = 32 / BITS;   // codes per 32-bit word
     const int lane = threadIdx.x & 63;
     const Selection sel = obtain_selection<SELECT_NCH>(x, K, k, idx_g, xsel_g, bid);
     const int32_t* idx = sel.idx;
@@ -173,15 +177,15 @@ __device__ __forceinline__ void fetch_int4_block(const FetchJobs& jobs, const Fi
     const int N = jobs.N[t.m];
     const uint4* __restrict__ R = jobs.R[t.m];
     const uint16_t* __restrict__ Rs = jobs.Rs[t.m];
-    const int piece = t.wc * 64 + lane;  // 32 columns
-    const bool active = piece * 32 < N;
+    const int piece = t.wc * 64 + lane;
+    const bool active = piece * CPL < N;
     const int rows_per = (k + slices - 1) / slices;
     const int j0 = t.rs * rows_per, j1 = min(j0 + rows_per, k);
-    const size_t row16 = (size_t)(N / 32);
+    const size_t row16 = (size_t)(N / CPL);
 
-    float acc[32];
+    float acc[CPL];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
+    for (int i = 0; i < CPL; ++i) acc[i] = 0.f;
     for (int j = j0; j < j1; j += kUnroll) {
         uint4 v[kUnroll];
         float xs[kUnroll];
@@ -203,32 +207,35 @@ __device__ __forceinline__ void fetch_int4_block(const FetchJobs& jobs, const Fi
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int q = (int)(w[c] << (28 - 4 * i)) >> 28;  // 4-bit two's complement
-                    acc[8 * c + i] = fmaf((float)q, xs[u], acc[8 * c + i]);
+                for (int i = 0; i < CPW; ++i) {
+                    const int q = (int)(w[c] << (32 - BITS * (i + 1))) >> (32 - BITS);  // two's complement field
+                    acc[CPW * c + i] = fmaf((float)q, xs[u], acc[CPW * c + i]);
                 }
             }
         }
     }
     if (active) {
-        const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * 32);
-        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * 32;
+        const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * CPL);
+        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * CPL;
         const bool coherent = fa.counters != nullptr;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < CPL / 8; ++b) {
             const uint4 sv = s4[b];
             const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w};
-            float r[8];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                r[2 * c] = acc[8 * b + 2 * c] * h2f(sw[c] & 0xFFFFu);
-                r[2 * c + 1] = acc[8 * b + 2 * c + 1] * h2f(sw[c] >> 16);
+                store_partial(out + 8 * b + 2 * c, acc[8 * b + 2 * c] * h2f(sw[c] & 0xFFFFu), coherent);
+                store_partial(out + 8 * b + 2 * c + 1, acc[8 * b + 2 * c + 1] * h2f(sw[c] >> 16), coherent);
             }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) store_partial(out + 8 * b + i, r[i], coherent);
         }
     }
-    if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, t.m, t.wc * 32, min(32, N / 64 - t.wc * 32), lane);
+    if (fa.counters != nullptr)
+        tiles_arrive_and_finalize(fa, t.m, t.wc * CPL, min(CPL, N / 64 - t.wc * CPL), lane);
+}
+
+// Columns one wavefront covers per row load, by residual format (decdec_rfmt).
+__host__ __device__ constexpr int fetch_cols_per_wave(int rfmt) {
+    return rfmt == 0 ? 512 : rfmt == 1 ? 2048 : rfmt == 2 ? 4096 : 1024;
 }
 
 }  // namespace decdec

@@ -11,7 +11,8 @@
 // runs 5-7x slower.  Inside one grid the fetch workgroups are dispatched first
 // (lowest workgroup ids), the GEMV workgroups fill the rest of the chip and
 // finish while the fetch workgroups are still waiting for the host link, and
-// nothing has to be joined.  How many workgroups fetch (the paper's n_tb,
+// nothing has to be joined.  (fp16 and 4-bit residuals; the 2- and 8-bit variants
+// of the bit-width study use the separate kernels.)  How many workgroups fetch (the paper's n_tb,
 // Section 4.4) is the row split of the residual kernel.
 #include <hip/hip_runtime.h>
 
@@ -31,7 +32,7 @@ __global__ __launch_bounds__(kBlockThreads) void compensated_gemv_kernel(
         if constexpr (RFMT == 0) {
             fetch_fp16_block<SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
         } else {
-            fetch_int4_block<SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
+            fetch_int_block<4, SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
         }
     } else {
         gemv_block<KIND, kWavesPerBlock>(gjobs, fa, reinterpret_cast<const uint32_t*>(x), gpart, Ntot, G, gslices, gpw, bid - nfetch);
@@ -76,11 +77,12 @@ hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, con
                                    const FetchOperands& fop, const void* x, int select_chunks, int32_t* idx, void* xsel,
                                    int k, float* gpart, int gslices, int gpw, float* cpart, int cslices,
                                    const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm) {
+    if (rfmt != 0 && rfmt != 1) return hipErrorInvalidValue;  // built for fp16 and 4-bit residuals only
     const int G = sh.K / kGroup;
     GemvJobs gj{};
     FetchJobs fj{};
     gj.n = fj.n = sh.n;
-    const int cpw = rfmt == 0 ? 512 : 2048;  // columns one wavefront covers per row load
+    const int cpw = fetch_cols_per_wave(rfmt);  // columns one wavefront covers per row load
     int tiles = 0, wc = 0;
     for (int m = 0; m < sh.n; ++m) {
         gj.Wq[m] = static_cast<const uint4*>(gop.Wq[m]);

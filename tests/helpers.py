@@ -8,6 +8,8 @@ import torch
 import oracle
 import paper_2412_20185_amd as dd
 
+RBITS = {"int2": 2, "int4": 4, "int8": 8}
+RFMT = {"fp16": dd.R_FP16, "int4": dd.R_INT4_SYM_COL, "int2": dd.R_INT2_SYM_COL, "int8": dd.R_INT8_SYM_COL}
 TOL_Y = 2e-3          # max relative error of y against the fp64 oracle (floor 1 % of rms on the denominator)
 
 
@@ -23,19 +25,19 @@ class Problem:
             self.codes, self.scales, self.zeros = oracle.quantize_uniform(W, bits)
             self.lut = None
             W_hat = oracle.dequantize_uniform(self.codes, self.scales, self.zeros)
-            self.desc = dd.Desc(K, N, bits, dd.W_UNIFORM_G128, dd.R_FP16 if rfmt == "fp16" else dd.R_INT4_SYM_COL)
+            self.desc = dd.Desc(K, N, bits, dd.W_UNIFORM_G128, RFMT[rfmt])
         else:
             self.codes, self.lut = oracle.quantize_lut(W, iters=lut_iters)
             self.scales = self.zeros = None
             W_hat = oracle.dequantize_lut(self.codes, self.lut)
-            self.desc = dd.Desc(K, N, 3, dd.W_LUT_COL8, dd.R_FP16 if rfmt == "fp16" else dd.R_INT4_SYM_COL)
+            self.desc = dd.Desc(K, N, 3, dd.W_LUT_COL8, RFMT[rfmt])
         if rfmt == "fp16":
             self.R = oracle.residual_fp16(W, W_hat)
             self.R_real = self.R
             self.Rq = self.Rs = None
         else:
             kw = {} if alphas is None else {"alphas": alphas}
-            self.Rq, self.Rs = oracle.quantize_residual_int4(W.astype(np.float64) - W_hat, **kw)
+            self.Rq, self.Rs = oracle.quantize_residual_sym(W.astype(np.float64) - W_hat, RBITS[rfmt], **kw)
             self.R_real = oracle.dequantize_residual_int4(self.Rq, self.Rs)
             self.R = None
         self.W_hat = W_hat if keep_dense else None
@@ -56,7 +58,7 @@ class Problem:
                 d["R"] = torch.from_numpy(self.R).pin_memory()
                 d["Rs"] = None
             else:
-                d["R"] = torch.from_numpy(dd.decdec_pack_residual_int4(self.Rq)).pin_memory()
+                d["R"] = torch.from_numpy(dd.decdec_pack_residual_int(self.Rq, RBITS[self.rfmt])).pin_memory()
                 d["Rs"] = torch.from_numpy(self.Rs).cuda()
             self._dev = d
         return self._dev

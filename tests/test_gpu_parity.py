@@ -110,6 +110,38 @@ def test_int4_residuals(ws, wfmt, bits, K, N):
         assert_parity(y, y_ref, idx, sc, what=f"int4 {wfmt}{bits} {K}x{N} k={k}")
 
 
+@pytest.mark.parametrize("rfmt,qmax", [("int2", 1), ("int8", 127)])
+@pytest.mark.parametrize("wfmt,bits,K,N", [("uniform", 3, 1024, 1024), ("uniform", 4, 640, 192), ("lut", 3, 1536, 2112),
+                                           ("uniform", 3, 2048, 4160)])
+def test_int2_int8_residuals(ws, rfmt, qmax, wfmt, bits, K, N):
+    """The other integer widths of the residual bit-width study (Table 2); N = 4160 leaves a ragged
+    last wavefront for both (4096 / 1024 columns per wavefront)."""
+    W = workloads.weights(51, 0, 0, K, N)
+    p = Problem(W, bits, wfmt=wfmt, rfmt=rfmt, lut_iters=2, alphas=oracle.quantize.DEFAULT_ALPHAS[::10])
+    assert p.Rq.min() == -qmax and p.Rq.max() == qmax
+    for step, k in enumerate([1, workloads.k_for_kchunk(K, 15) or 3, K // 2, K]):
+        x = workloads.x_student_t(5, 1, 0, step, K, outlier_frac=0.005, outlier_mult=30.0)
+        y_ref, sc = p.reference(x, k)
+        y, idx, _ = p.run(x, k, ws)
+        assert_parity(y, y_ref, idx, sc, what=f"{rfmt} {wfmt}{bits} {K}x{N} k={k}")
+    # q+k+v style group through the multi entry point
+    if wfmt == "uniform":
+        x = workloads.x_student_t(5, 1, 0, 9, K, outlier_frac=0.005, outlier_mult=30.0)
+        k = max(1, K // 50)
+        y_ref, sc = p.reference(x, k)
+        d = p.device()
+        xd = torch.from_numpy(x).cuda()
+        y2 = torch.full((2 * N,), float("nan"), dtype=torch.float16, device="cuda")
+        lin = dd.make_linears([(p.desc, d["Wq"], d["scales"], d["zl"], d["R"], d["Rs"], y2[:N]),
+                               (p.desc, d["Wq"], d["scales"], d["zl"], d["R"], d["Rs"], y2[N:])])
+        dd.decdec_gemv_multi(lin, xd, k, ws)
+        torch.cuda.synchronize()
+        idx, _ = ws.read_selection(k)
+        yh = y2.cpu().numpy()
+        assert_parity(yh[:N], y_ref, idx, sc, what=f"{rfmt} multi[0]")
+        assert np.array_equal(yh[:N].view(np.uint16), yh[N:].view(np.uint16))
+
+
 def test_caller_supplied_selection_matches_internal_selection(ws):
     """q/k/v share one x: select once, reuse the indices (decdec_gemv_idx)."""
     K, N = 2048, 512

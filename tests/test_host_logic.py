@@ -36,7 +36,7 @@ def test_strerror_and_buffer_size():
 def test_validation_without_gpu():
     L = dd.lib()
     bad = [dd.Desc(100, 64, 4), dd.Desc(128, 60, 4), dd.Desc(128, 64, 5), dd.Desc(128, 64, 4, wfmt=7),
-           dd.Desc(128, 64, 4, rfmt=3), dd.Desc(0, 64, 4)]
+           dd.Desc(128, 64, 4, rfmt=4), dd.Desc(0, 64, 4)]
     for d in bad:
         assert dd.decdec_packed_bytes(d) == 0
         assert L.decdec_gemv(C.byref(d), 1, 1, 1, 1, 1, 1, 0, 1, 1, None) == -1
@@ -151,3 +151,19 @@ def test_int4_residual_rows():
     assert out.shape == (2, 32)
     assert out[0, 0] == ((-7) & 0xF) | (7 << 4) and out[0, 1] == 0 | (((-1) & 0xF) << 4)
     assert out[1, 0] == 1 | (2 << 4) and out[1, 1] == 3 | (4 << 4)
+
+
+def test_int2_int8_residual_rows():
+    """2-bit: column 4j+i in bits 2i..2i+1 of byte j; 8-bit: one two's-complement byte per column."""
+    q = np.array([[-1, 1, 0, -1] * 16, [1, 0, 0, 1] * 16], np.int8)
+    out = dd.decdec_pack_residual_int(q, 2)
+    assert out.shape == (2, 16)
+    assert out[0, 0] == (3 | (1 << 2) | (0 << 4) | (3 << 6)) and out[1, 0] == (1 | (1 << 6))
+    q8 = np.array([[-127, 127, 0, -1] * 4], np.int8)
+    out = dd.decdec_pack_residual_int(q8, 8)
+    assert out.shape == (1, 16) and np.array_equal(out.view(np.int8), q8)
+    assert np.array_equal(dd.decdec_pack_residual_int(np.tile(q8, (1, 2)), 4 * 2)[:, :16].view(np.int8), q8)
+    for bad, bits in ((np.full((1, 64), 2, np.int8), 2), (np.full((1, 16), -128, np.int8), 8),
+                      (np.zeros((1, 8), np.int8), 8), (np.zeros((1, 64), np.int8), 3)):
+        with pytest.raises(dd.DecdecError):
+            dd.decdec_pack_residual_int(bad, bits)

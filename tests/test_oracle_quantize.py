@@ -256,3 +256,77 @@ def test_int4_codes_range_and_error_bound():
     S1 = (np.abs(R).max(0) / 7).astype(np.float16).astype(np.float64)
     e1 = ((R - S1 * np.clip(np.rint(R / S1), -7, 7)) ** 2).sum(0)
     assert np.all(((R - Rh) ** 2).sum(0) <= e1 * (1 + 1e-12))
+
+
+def brute_sym(R, bits, alphas):
+    """Column by column in Python floats: the grid search written out for any code width."""
+    qmax = float(2 ** (bits - 1) - 1)
+    K, N = R.shape
+    q = np.zeros((K, N), np.int8)
+    S = np.zeros(N, np.float16)
+    for n in range(N):
+        col = [float(v) for v in R[:, n]]
+        m = max(abs(v) for v in col)
+        best_err, best_s = float("inf"), None
+        for a in alphas:
+            s16 = np.float16(float(a) * m / qmax)
+            if s16 == 0:
+                s16 = np.float16(1)
+            s = float(s16)
+            err = sum((v - s * min(max(float(np.rint(v / s)), -qmax), qmax)) ** 2 for v in col)
+            if err <= best_err:
+                best_err, best_s = err, s16
+        S[n] = best_s
+        for k, v in enumerate(col):
+            q[k, n] = int(min(max(float(np.rint(v / float(best_s))), -qmax), qmax))
+    return q, S
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_symmetric_residual_quantiser_widths(bits):
+    """Table 2's integer widths: brute force, a residual already on the grid, code range, and the
+    half-step error bound for every value the clip does not touch."""
+    qmax = 2 ** (bits - 1) - 1
+    g = np.random.default_rng(210 + bits)
+    R = g.standard_normal((80, 5)) * 1e-3
+    R[:, 3] = 0.0
+    alphas = oq.DEFAULT_ALPHAS[::7]
+    q, S = oracle.quantize_residual_sym(R, bits, alphas)
+    bq, bS = brute_sym(R, bits, alphas)
+    assert np.array_equal(q, bq) and np.array_equal(S, bS)
+    assert S[3] == np.float16(1) and not q[:, 3].any()
+    # on-grid residual is reproduced exactly, with the power-of-two scale it was built from
+    q0 = g.integers(-qmax, qmax + 1, size=(64, 3))
+    q0[0] = qmax
+    S0 = np.array([2.0 ** -10, 2.0 ** -12, 2.0 ** -9])
+    q, S = oracle.quantize_residual_sym(q0 * S0, bits)
+    assert np.array_equal(q, q0.astype(np.int8)) and np.array_equal(S.astype(np.float64), S0)
+    # range and error bound on a larger draw
+    R = g.standard_normal((1024, 16)) * 2e-3
+    q, S = oracle.quantize_residual_sym(R, bits)
+    assert q.min() >= -qmax and q.max() <= qmax
+    Sd = S.astype(np.float64)
+    inside = np.abs(R / Sd) <= qmax + 0.5
+    err = np.abs(R - oracle.dequantize_residual_int4(q, S))
+    assert np.all(err[inside] <= np.broadcast_to(Sd / 2, R.shape)[inside] * (1 + 1e-12))
+    if bits == 4:
+        q4, S4 = oracle.quantize_residual_int4(R)
+        assert np.array_equal(q, q4) and np.array_equal(S, S4)
+
+
+def test_residual_width_ordering_and_ternary_closed_form():
+    """More bits never lose at equal k; a column uniform on [-a, a] quantised to {-S, 0, S} has its
+    least squared error at S = 2a/3 (thresholds at +-a/3), error a^2/27 per element."""
+    g = np.random.default_rng(77)
+    R = g.uniform(-1e-3, 1e-3, size=(20000, 3))
+    mse = []
+    for bits in (2, 4, 8):
+        q, S = oracle.quantize_residual_sym(R, bits)
+        mse.append(((R - oracle.dequantize_residual_int4(q, S)) ** 2).mean(0))
+    assert np.all(mse[0] > mse[1]) and np.all(mse[1] > mse[2])
+    _, S2 = oracle.quantize_residual_sym(R, 2)
+    a = np.abs(R).max(0)
+    assert np.all(np.abs(S2.astype(np.float64) / a - 2 / 3) < 0.03)
+    assert np.all(np.abs(mse[0] / (a ** 2 / 27) - 1) < 0.03)
+    with pytest.raises(ValueError):
+        oracle.quantize_residual_sym(R, 3)
