@@ -6,6 +6,8 @@
                                                        next to the knee model of the paper (Section 5.1)
     python -m paper_2412_20185_amd.microbench select   exact radix select versus the paper's approximate bucket
                                                        Top-K (Section 4.3): time per launch and recall
+    python -m paper_2412_20185_amd.microbench rformats residual formats of the bit-width study (Table 2) at equal link
+                                                       bytes: fetch kernel time and link rate for 2/4/8-bit and fp16 rows
     python -m paper_2412_20185_amd.microbench tune     the paper's parameter tuner (Section 4.4) on this GPU:
                                                        fetch workgroups and k_chunk per layer type for target slowdowns
 
@@ -102,6 +104,51 @@ def fetch(args):
         print(line, flush=True)
         del R
     ws.set_fetch_split(0)
+    ws.close()
+
+
+def rformats(args):
+    """Table 2's design on the link: k_chunk channels per 1024 with 4-bit rows move as many bytes as
+    2 k_chunk with 2-bit, k_chunk / 2 with 8-bit and k_chunk / 4 with fp16 rows.  Separate kernels
+    (serial mode) so that the fetch kernel's own duration is what is reported."""
+    ws = B.Workspace(28672, 28672, 8192)
+    ws.set_mode(B.MODE_SERIAL)
+    ws.set_separate_select(True)
+    fmts = [("2-bit", B.R_INT2_SYM_COL, 2, 2.0), ("4-bit", B.R_INT4_SYM_COL, 4, 1.0),
+            ("8-bit", B.R_INT8_SYM_COL, 8, 0.5), ("fp16", B.R_FP16, 16, 0.25)]
+    print("fetch kernel at equal link bytes: us / GB/s (rows + scales) per residual format")
+    print(f"{'K':>6s} {'N':>6s} {'k_chunk(4b)':>11s} {'MB':>6s}  " + "  ".join(f"{f[0]:>14s}" for f in fmts))
+    for K, N in ((4096, 4096), (4096, 14336), (14336, 4096)):
+        rows = {}
+        for name, rfmt, bits, _ in fmts:
+            R = torch.empty((K, N * bits // 8), dtype=torch.uint8, pin_memory=True)
+            R.random_(0, 256)
+            if bits == 16:  # keep fp16 payloads finite
+                R.view(torch.float16).normal_(0, 0.003)
+            rows[name] = R
+        Rs = torch.full((N,), 1e-3, dtype=torch.float16, device="cuda")
+        xs = [torch.randn(K, device="cuda").half() for _ in range(8)]
+        y = torch.empty(N, dtype=torch.float16, device="cuda")
+        for kc4 in (8, 32, 128):
+            line = f"{K:6d} {N:6d} {kc4:11d} {kc4 * (K // 1024) * N / 2 / 1e6:6.2f}  "
+            for name, rfmt, bits, mult in fmts:
+                k = int(kc4 * mult) * (K // 1024)
+                d = B.Desc(K, N, 3, B.W_UNIFORM_G128, rfmt)
+                _, Wq, sc, zl, _ = _operands(K, N, 3, B.W_UNIFORM_G128, copies_bytes=0)
+                scales = None if bits == 16 else Rs
+                for i in range(3):
+                    B.decdec_gemv(d, xs[i % 8], Wq[0], sc, zl, rows[name], scales, k, y, ws)
+                torch.cuda.synchronize()
+                ws.set_profiling(args.reps)
+                for i in range(args.reps):
+                    B.decdec_gemv(d, xs[i % 8], Wq[0], sc, zl, rows[name], scales, k, y, ws)
+                ms, n = ws.read_profile()["fetch"]
+                ws.set_profiling(0)
+                us = ms * 1e3 / n
+                nbytes = k * N * bits / 8 + (0 if bits == 16 else 2 * N)
+                line += f"  {us:7.1f} / {nbytes / us / 1e3:4.1f}"
+            print(line, flush=True)
+        del rows
     ws.close()
 
 
@@ -280,7 +327,7 @@ def tune(args):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select", "tune"))
+    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select", "rformats", "tune"))
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=12)
@@ -291,7 +338,7 @@ def main():
         print("needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select, "tune": tune}[args.what](args)
+    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "tune": tune}[args.what](args)
     return 0
 
 

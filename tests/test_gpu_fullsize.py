@@ -52,21 +52,35 @@ def test_llama3_8b_down_int4_residuals(ws):
         assert_parity(y, y_ref, idx, sc, what="8B down int4")
 
 
+def _drawn_residual(g, K, N, rfmt):
+    """Stored residual parameters drawn directly: (pinned tensor, device scales or None, fetch(s, n) -> fp64)."""
+    if rfmt == "fp16":
+        R = (g.standard_normal((K, N), dtype=np.float32) * np.float32(0.003)).astype(np.float16)
+        return torch.from_numpy(R).pin_memory(), None, lambda s, n: R[s, n].astype(np.float64)
+    bits = {"int2": 2, "int4": 4, "int8": 8}[rfmt]
+    qmax = 2 ** (bits - 1) - 1
+    q = g.integers(-qmax, qmax + 1, size=(K, N), dtype=np.int8)
+    S = (np.abs(g.standard_normal(N)) * 0.004 / qmax + 1e-5).astype(np.float16)
+    packed = torch.from_numpy(dd.decdec_pack_residual_int(q, bits)).pin_memory()
+    return packed, torch.from_numpy(S).cuda(), lambda s, n: q[s, n].astype(np.float64) * float(S[n])
+
+
+@pytest.mark.parametrize("rfmt", ["fp16", "int4", "int2", "int8"])
 @pytest.mark.parametrize("K,N", [(8192, 28672), (28672, 8192), (8192, 1024)])
-def test_llama3_70b_lut_shapes_sampled(ws, K, N):
-    """Config 4: 3-bit codebook weights, Student-t activations, k = 1 % of K."""
+def test_llama3_70b_lut_shapes_sampled(ws, K, N, rfmt):
+    """Config 4: 3-bit codebook weights, Student-t activations, k = 1 % of K; with fp16 residuals as the
+    config states and with the integer residual formats of Table 2."""
     g = np.random.default_rng([4, K, N])
     codes = g.integers(0, 8, size=(K, N), dtype=np.uint8)
     lut = np.sort(g.standard_normal((N, 8)) * 0.02, axis=1).astype(np.float16)
-    R = (g.standard_normal((K, N), dtype=np.float32) * np.float32(0.003)).astype(np.float16)
-    desc = dd.Desc(K, N, 3, dd.W_LUT_COL8, dd.R_FP16)
+    R_p, Rs_d, r_at = _drawn_residual(g, K, N, rfmt)
+    desc = dd.Desc(K, N, 3, dd.W_LUT_COL8, dd.R_FMT_OF_BITS[{"fp16": 16, "int4": 4, "int2": 2, "int8": 8}[rfmt]])
     Wq = torch.from_numpy(dd.decdec_pack_weights(desc, codes)).cuda()
     lut_d = torch.from_numpy(lut).cuda()
-    R_p = torch.from_numpy(R).pin_memory()
     k = workloads.k_for_fraction(K, 0.01)
     x = workloads.x_student_t(4, 0, "down_in" if K > N else "mlp_in", 0, K)
     y = torch.empty(N, dtype=torch.float16, device="cuda")
-    dd.decdec_gemv(desc, torch.from_numpy(x).cuda(), Wq, None, lut_d, R_p, None, k, y, ws)
+    dd.decdec_gemv(desc, torch.from_numpy(x).cuda(), Wq, None, lut_d, R_p, Rs_d, k, y, ws)
     torch.cuda.synchronize()
     idx, xsel = ws.read_selection(k)
     sc = oracle.topk_abs(x, k)
@@ -75,10 +89,47 @@ def test_llama3_70b_lut_shapes_sampled(ws, K, N):
     cols = np.sort(g.choice(N, 96, replace=False))
     cols[0], cols[-1] = 0, N - 1
     lut64 = lut.astype(np.float64)
-    y_ref = oracle.compensated_gemv_columns(lambda n: lut64[n][codes[:, n]], x,
-                                            lambda s, n: R[s, n].astype(np.float64), sc, cols)
+    y_ref = oracle.compensated_gemv_columns(lambda n: lut64[n][codes[:, n]], x, r_at, sc, cols)
     rms = float(np.sqrt(np.mean(y_ref ** 2)))
     err = oracle.error_metric(y.cpu().numpy().astype(np.float64)[cols], y_ref, rms=rms)
     assert np.all(np.isfinite(y.cpu().numpy().astype(np.float64)))
     assert err <= TOL_Y, err
-    print(f"70B {K}x{N} lut3 k={k}: rel err on 96 sampled columns {err:.2e}")
+    print(f"70B {K}x{N} lut3 {rfmt} k={k}: rel err on 96 sampled columns {err:.2e}")
+
+
+@pytest.mark.parametrize("rfmt", ["int4", "int2", "int8"])
+@pytest.mark.parametrize("bits", [3, 4])
+def test_llama3_8b_gate_up_integer_residuals_sampled(ws, bits, rfmt):
+    """Configs 2 and 3 with the integer residual formats: gate and up (4096 -> 14336 each) through the
+    multi entry point, k = 2 % of K; stored parameters drawn directly, sampled columns checked."""
+    K, N = 4096, 14336
+    g = np.random.default_rng([23, bits, len(rfmt), ord(rfmt[-1])])
+    desc = dd.Desc(K, N, bits, dd.W_UNIFORM_G128, dd.R_FMT_OF_BITS[int(rfmt[3:])])
+    k = workloads.k_for_fraction(K, 0.02)
+    x = workloads.x_gauss_outliers(2, 0, "mlp_in", 3, K)
+    sc = oracle.topk_abs(x, k)
+    mats, ys = [], []
+    for m in range(2):
+        codes = g.integers(0, 2 ** bits, size=(K, N), dtype=np.uint8)
+        scales = (np.abs(g.standard_normal((K // 128, N))) * 0.01 + 1e-3).astype(np.float16)
+        zeros = g.integers(0, 2 ** bits, size=(K // 128, N)).astype(np.float16)
+        R_p, Rs_d, r_at = _drawn_residual(g, K, N, rfmt)
+        y = torch.full((N,), float("nan"), dtype=torch.float16, device="cuda")
+        mats.append((codes, scales, zeros, r_at))
+        ys.append(y)
+        mats[-1] += ((desc, torch.from_numpy(dd.decdec_pack_weights(desc, codes)).cuda(),
+                      torch.from_numpy(scales).cuda(), torch.from_numpy(zeros).cuda(), R_p, Rs_d, y),)
+    lin = dd.make_linears([m[4] for m in mats])
+    dd.decdec_gemv_multi(lin, torch.from_numpy(x).cuda(), k, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(ws.read_selection(k)[0], sc)
+    for (codes, scales, zeros, r_at, _), y in zip(mats, ys):
+        cols = np.sort(g.choice(N, 64, replace=False))
+        cols[0], cols[-1] = 0, N - 1
+        s64, z64 = scales.astype(np.float64), zeros.astype(np.float64)
+        col = lambda n: np.repeat(s64[:, n], 128) * (codes[:, n].astype(np.float64) - np.repeat(z64[:, n], 128))
+        y_ref = oracle.compensated_gemv_columns(col, x, r_at, sc, cols)
+        yh = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(yh))
+        err = oracle.error_metric(yh[cols], y_ref, rms=float(np.sqrt(np.mean(y_ref ** 2))))
+        assert err <= TOL_Y, err
