@@ -122,18 +122,22 @@ __device__ __forceinline__ void fetch_fp16_block(const FetchJobs& jobs, const Fi
     for (int j = j0; j < j1; j += kUnroll) {
         uint4 v[kUnroll];
         float xs[kUnroll];
+        int row[kUnroll];
+        uint32_t xraw[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {  // indices and activations first, so that no row load waits for them
+            const int jj = min(j + u, j1 - 1);
+            row[u] = idx[jj];
+            xraw[u] = xsel[jj];
+        }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             v[u] = make_uint4(0, 0, 0, 0);
-            xs[u] = 0.f;
-            if (j + u < j1) {
-                const int row = idx[j + u];
-                if (active && (unsigned)row < (unsigned)K) {
-                    v[u] = R[(size_t)row * row16 + oct];
-                    xs[u] = h2f(xsel[j + u]);
-                }
-            }
+            if (j + u < j1 && active && (unsigned)row[u] < (unsigned)K) v[u] = R[(size_t)row[u] * row16 + oct];
         }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            xs[u] = (j + u < j1 && (unsigned)row[u] < (unsigned)K) ? h2f(xraw[u]) : 0.f;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
@@ -183,26 +187,38 @@ __device__ __forceinline__ void fetch_int_block(const FetchJobs& jobs, const Fin
     const int j0 = t.rs * rows_per, j1 = min(j0 + rows_per, k);
     const size_t row16 = (size_t)(N / CPL);
 
+    // The column scales are requested before the rows, so that they arrive behind the first row loads
+    // instead of costing a round trip of their own after the last one.
+    uint4 sv[CPL / 8];
+#pragma unroll
+    for (int b = 0; b < CPL / 8; ++b)
+        sv[b] = active ? reinterpret_cast<const uint4*>(Rs + (size_t)piece * CPL)[b] : make_uint4(0, 0, 0, 0);
+
     float acc[CPL];
 #pragma unroll
     for (int i = 0; i < CPL; ++i) acc[i] = 0.f;
     for (int j = j0; j < j1; j += kUnroll) {
         uint4 v[kUnroll];
         float xs[kUnroll];
+        int row[kUnroll];
+        uint32_t xraw[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            v[u] = make_uint4(0, 0, 0, 0);
-            xs[u] = 0.f;
-            if (j + u < j1) {
-                const int row = idx[j + u];
-                if (active && (unsigned)row < (unsigned)K) {
-                    v[u] = R[(size_t)row * row16 + piece];
-                    xs[u] = h2f(xsel[j + u]);
-                }
-            }
+        for (int u = 0; u < kUnroll; ++u) {  // indices and activations first, so that no row load waits for them
+            const int jj = min(j + u, j1 - 1);
+            row[u] = idx[jj];
+            xraw[u] = xsel[jj];
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
+            v[u] = make_uint4(0, 0, 0, 0);
+            if (j + u < j1 && active && (unsigned)row[u] < (unsigned)K) v[u] = R[(size_t)row[u] * row16 + piece];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            xs[u] = (j + u < j1 && (unsigned)row[u] < (unsigned)K) ? h2f(xraw[u]) : 0.f;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (j + u >= j1) break;  // wave-uniform: a short slice does not pay for the rows it does not have
             const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -215,18 +231,23 @@ __device__ __forceinline__ void fetch_int_block(const FetchJobs& jobs, const Fin
         }
     }
     if (active) {
-        const uint4* s4 = reinterpret_cast<const uint4*>(Rs + (size_t)piece * CPL);
-        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * CPL;
-        const bool coherent = fa.counters != nullptr;
 #pragma unroll
         for (int b = 0; b < CPL / 8; ++b) {
-            const uint4 sv = s4[b];
-            const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w};
+            const uint32_t sw[4] = {sv[b].x, sv[b].y, sv[b].z, sv[b].w};
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                store_partial(out + 8 * b + 2 * c, acc[8 * b + 2 * c] * h2f(sw[c] & 0xFFFFu), coherent);
-                store_partial(out + 8 * b + 2 * c + 1, acc[8 * b + 2 * c + 1] * h2f(sw[c] >> 16), coherent);
+                acc[8 * b + 2 * c] *= h2f(sw[c] & 0xFFFFu);
+                acc[8 * b + 2 * c + 1] *= h2f(sw[c] >> 16);
             }
+        }
+        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + (size_t)piece * CPL;
+        if (fa.counters != nullptr) {
+#pragma unroll
+            for (int i = 0; i < CPL; ++i) store_partial(out + i, acc[i], true);
+        } else {
+#pragma unroll
+            for (int i = 0; i < CPL / 4; ++i)
+                reinterpret_cast<float4*>(out)[i] = make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
         }
     }
     if (fa.counters != nullptr)
