@@ -271,6 +271,28 @@ int decdec_quantize_uniform(const decdec_desc* d, const void* W_f32_dev, void* W
                             void* scales_f16_out_dev, void* zeros_f16_out_dev,
                             void* R_f16_out, void* stream);
 
+/* R = W - W_hat for weights that are already quantised and packed (Section 3.1;
+ * any base quantiser, as the paper applies the method on top of third-party
+ * ones, Section 5.2): one fp32 subtraction per element, W_hat = s (q - z)
+ * (exact in fp32) or the codebook entry.
+ *   W_f32_dev dev fp32 [K][N];  Wq_dev / scales / zeros_or_lut as for decdec_gemv
+ *   (scales NULL for LUT_COL8);  R_f32_out_dev dev fp32 [K][N] out. */
+int decdec_residual_f32(const decdec_desc* d, const void* W_f32_dev, const void* Wq_dev, const void* scales_f16_dev,
+                        const void* zeros_or_lut_f16_dev, void* R_f32_out_dev, void* stream);
+
+/* The residual quantiser (Section 4.2; bits = 4 is the paper's, 2 and 8 the
+ * other integer widths of Table 2): per output column n
+ *   q[k][n] = clip(rint(R[k][n] / S[n]), -qmax, qmax),  qmax = 2^(bits-1) - 1,
+ * S[n] the value of fp16(alpha max_k|R[k][n]| / qmax), alpha = 0.30, 0.31, ...,
+ * 1.00, with the least sum_k (R - S q)^2 (a tie keeps the larger alpha; a
+ * column whose scale rounds to 0 gets S = 1).  Every step is one IEEE fp64
+ * operation and a column's error is summed over k in ascending order.
+ *   R_f32_dev dev fp32 [K][N] in;  codes_out dev or pinned bytes [K][N*bits/8],
+ *   the layout of decdec_pack_residual_int;  scales_f16_out_dev dev fp16 [N];
+ *   N a multiple of 128 / bits. */
+int decdec_quantize_residual(int32_t K, int32_t N, int32_t bits, const void* R_f32_dev, void* codes_out,
+                             void* scales_f16_out_dev, void* stream);
+
 /* ------------------------------------------------------------ diagnostics */
 const char* decdec_strerror(int status);
 int decdec_last_hip_error(void); /* hipError_t of the last failing HIP call on this thread */

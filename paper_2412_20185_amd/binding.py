@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = (
     "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_pack_residual_int", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
-    "decdec_quantize_uniform", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
+    "decdec_quantize_uniform", "decdec_residual_f32", "decdec_quantize_residual", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
 )
 
 
@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
     L.decdec_gemv.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     L.decdec_gemv_idx.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     L.decdec_quantize_uniform.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    L.decdec_residual_f32.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    L.decdec_quantize_residual.argtypes = [i32, i32, i32, vp, vp, vp, vp]
     L.decdec_gemv_multi.argtypes = [i32, C.POINTER(Linear), vp, i32, vp, vp]
     _lib = L
     return L
@@ -277,3 +279,13 @@ def decdec_gemv_multi(linears, x, k: int, ws: Workspace, stream=None):
 def decdec_quantize_uniform(desc: Desc, W_f32, Wq_out, scales_out, zeros_out, R_out=None, stream=None):
     _check(lib().decdec_quantize_uniform(C.byref(desc), _ptr(W_f32), _ptr(Wq_out), _ptr(scales_out),
                                          _ptr(zeros_out), _ptr(R_out), _stream(stream)), "decdec_quantize_uniform")
+
+
+def decdec_residual_f32(desc: Desc, W_f32, Wq, scales, zeros_or_lut, R_f32_out, stream=None):
+    _check(lib().decdec_residual_f32(C.byref(desc), _ptr(W_f32), _ptr(Wq), _ptr(scales), _ptr(zeros_or_lut),
+                                     _ptr(R_f32_out), _stream(stream)), "decdec_residual_f32")
+
+
+def decdec_quantize_residual(K: int, N: int, bits: int, R_f32, codes_out, scales_out, stream=None):
+    _check(lib().decdec_quantize_residual(K, N, bits, _ptr(R_f32), _ptr(codes_out), _ptr(scales_out),
+                                          _stream(stream)), "decdec_quantize_residual")

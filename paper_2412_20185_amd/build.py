@@ -8,7 +8,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdecdec.so")
-SOURCES = ("api.hip", "gemv.hip", "select.hip", "select_bucket.hip", "fetch.hip", "fused.hip", "accumulate.hip", "quantize.hip")
+SOURCES = ("api.hip", "gemv.hip", "select.hip", "select_bucket.hip", "fetch.hip", "fused.hip", "accumulate.hip", "quantize.hip",
+           "residual_quantize.hip")
 
 
 def build(verbose: bool = False) -> str:

@@ -573,4 +573,28 @@ int decdec_quantize_uniform(const decdec_desc* d, const void* W_f32_dev, void* W
     return DECDEC_OK;
 }
 
+int decdec_residual_f32(const decdec_desc* d, const void* W_f32_dev, const void* Wq_dev, const void* scales_f16_dev,
+                        const void* zeros_or_lut_f16_dev, void* R_f32_out_dev, void* stream) {
+    const int rc = check_desc(d);
+    if (rc != DECDEC_OK) return rc;
+    if (W_f32_dev == nullptr || Wq_dev == nullptr || zeros_or_lut_f16_dev == nullptr || R_f32_out_dev == nullptr)
+        return DECDEC_EINVAL;
+    if (d->wfmt == DECDEC_W_UNIFORM_G128 && scales_f16_dev == nullptr) return DECDEC_EINVAL;
+    DD_HIP(launch_residual_f32(pack_kind(d), static_cast<const float*>(W_f32_dev), Wq_dev, scales_f16_dev,
+                               zeros_or_lut_f16_dev, static_cast<float*>(R_f32_out_dev), d->K, d->N,
+                               static_cast<hipStream_t>(stream)));
+    return DECDEC_OK;
+}
+
+int decdec_quantize_residual(int32_t K, int32_t N, int32_t bits, const void* R_f32_dev, void* codes_out,
+                             void* scales_f16_out_dev, void* stream) {
+    if (bits != 2 && bits != 4 && bits != 8) return DECDEC_EUNSUPPORTED;
+    if (K <= 0 || N <= 0 || N % (128 / bits) != 0 || R_f32_dev == nullptr || codes_out == nullptr ||
+        scales_f16_out_dev == nullptr)
+        return DECDEC_EINVAL;
+    DD_HIP(launch_quantize_residual(bits, static_cast<const float*>(R_f32_dev), codes_out, scales_f16_out_dev, K, N,
+                                    static_cast<hipStream_t>(stream)));
+    return DECDEC_OK;
+}
+
 }  // extern "C"

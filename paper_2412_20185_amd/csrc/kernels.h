@@ -107,5 +107,9 @@ hipError_t launch_clear_u32(unsigned* p, int n, hipStream_t stream);
 // quantize.hip -----------------------------------------------------------
 hipError_t launch_quantize_uniform(int bits, const float* W, void* Wq, void* scales, void* zeros, void* R, int K,
                                    int N, hipStream_t stream);
+hipError_t launch_residual_f32(int kind, const float* W, const void* Wq, const void* scales, const void* zeros_or_lut,
+                               float* R, int K, int N, hipStream_t stream);
+hipError_t launch_quantize_residual(int bits, const float* R, void* codes_out, void* scales_out, int K, int N,
+                                    hipStream_t stream);
 
 }  // namespace decdec
