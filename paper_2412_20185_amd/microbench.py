@@ -8,6 +8,9 @@
                                                        Top-K (Section 4.3): time per launch and recall
     python -m paper_2412_20185_amd.microbench rformats residual formats of the bit-width study (Table 2) at equal link
                                                        bytes: fetch kernel time and link rate for 2/4/8-bit and fp16 rows
+    python -m paper_2412_20185_amd.microbench configs  decode-step latency on the two larger workloads: a Llama-3-70B-shaped
+                                                       layer (3-bit codebook weights, fp16 residuals, k = 1 %) and a
+                                                       32-layer Llama-3-8B-shaped step with 4-bit residuals at k_chunk = 15
     python -m paper_2412_20185_amd.microbench tune     the paper's parameter tuner (Section 4.4) on this GPU:
                                                        fetch workgroups and k_chunk per layer type for target slowdowns
 
@@ -150,6 +153,94 @@ def rformats(args):
             print(line, flush=True)
         del rows
     ws.close()
+
+
+def _random_layer(shapes, wbits, wfmt, rbits, order, ys):
+    """Stored parameters of one decoder layer as random bytes (timing does not depend on the values;
+    fp16 residual payloads are kept finite), grouped by shared input."""
+    lin = {}
+    for name, K, N, _ in shapes:
+        d = B.Desc(K, N, wbits, wfmt, B.R_FMT_OF_BITS[rbits])
+        Wq = torch.randint(0, 256, (B.decdec_packed_bytes(d),), dtype=torch.uint8, device="cuda")
+        if wfmt == B.W_UNIFORM_G128:
+            sc = torch.full((K // 128, N), 0.01, dtype=torch.float16, device="cuda")
+            zl = torch.full((K // 128, N), 3.0, dtype=torch.float16, device="cuda")
+        else:
+            sc = None
+            zl = (torch.sort(torch.randn(N, 8, device="cuda"), dim=1).values * 0.02).half().contiguous()
+        R = torch.empty((K, N * rbits // 8), dtype=torch.uint8, pin_memory=True)
+        if rbits == 16:
+            R.view(torch.float16).copy_((torch.randn((K, N), device="cuda") * 0.003).half())
+            Rs = None
+        else:
+            R.copy_(torch.randint(0, 256, R.shape, dtype=torch.uint8, device="cuda"))
+            Rs = torch.full((N,), 1e-3, dtype=torch.float16, device="cuda")
+        lin[name] = (d, Wq, sc, zl, R, Rs, ys[name])
+    return [B.make_linears([lin[n] for n in names]) for _, names in order]
+
+
+def configs(args):
+    """Whole decode steps (every GEMV of every layer once) replayed as HIP graphs: wall time per step and
+    per GEMV with compensation and without (k = 0), bytes over the host link and the link rate they imply."""
+    import time
+    import workloads
+    order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
+    cases = [
+        ("Llama-3-70B-shaped layer, 3-bit codebook weights, fp16 residuals, k = 1 % of K, Student-t x",
+         workloads.LLAMA3_70B_LAYER, 3, B.W_LUT_COL8, 16, 2, lambda K: workloads.k_for_fraction(K, 0.01), 4),
+        ("32-layer Llama-3-8B-shaped step, 3-bit group-128 weights, 4-bit residuals, k_chunk = 15, Student-t x "
+         "with 0.5 % outlier channels x30",
+         workloads.LLAMA3_8B_LAYER, 3, B.W_UNIFORM_G128, 4, 32, lambda K: workloads.k_for_kchunk(K, 15), 5),
+    ]
+    for title, shapes, wbits, wfmt, rbits, nlayers, kof, cfg in cases:
+        ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
+        layers = [_random_layer(shapes, wbits, wfmt, rbits, order, ys) for _ in range(nlayers)]
+        Kof = {name: K for name, K, _, _ in shapes}
+        inputs = sorted({(w, K) for _, K, _, w in shapes})
+        extra = dict(outlier_frac=0.005, outlier_mult=30.0) if cfg == 5 else {}
+        xpool = [{w: torch.from_numpy(workloads.x_student_t(cfg, 0, w, s, K, **extra)).cuda() for w, K in inputs}
+                 for s in range(args.xpool)]
+        ws = B.Workspace(max(K for _, K, _, _ in shapes), 2 * max(N for _, _, N, _ in shapes), 2048)
+        stream = torch.cuda.Stream()
+        res = {}
+        for mode in ("compensated", "base"):
+            def step(i):
+                xs = xpool[i % args.xpool]
+                for l in range(nlayers):
+                    for (which, names), grp in zip(order, layers[l]):
+                        B.decdec_gemv_multi(grp, xs[which], kof(Kof[names[0]]) if mode == "compensated" else 0, ws)
+            graphs = []
+            for i in range(args.xpool):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    step(i)
+                graphs.append(g)
+            nsteps = max(4, args.steps // nlayers)
+            for i in range(2):
+                graphs[i % len(graphs)].replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(nsteps):
+                graphs[i % len(graphs)].replay()
+            torch.cuda.synchronize()
+            res[mode] = (time.perf_counter() - t0) * 1e6 / nsteps
+            del graphs
+        ngemv = nlayers * len(shapes)
+        rbytes = nlayers * sum(kof(K) * N * rbits // 8 for _, K, N, _ in shapes)
+        if wfmt == B.W_UNIFORM_G128:
+            wbytes = nlayers * sum(K * N * wbits // 8 + 4 * N * (K // 128) + 2 * K + 2 * N for _, K, N, _ in shapes)
+        else:
+            wbytes = nlayers * sum(K * N * wbits // 8 + 16 * N + 2 * K + 2 * N for _, K, N, _ in shapes)
+        print(title)
+        print(f"  {ngemv} GEMVs per step; weights {wbytes / 1e6:.1f} MB, residual rows over the link {rbytes / 1e6:.2f} MB "
+              f"({100 * rbytes / wbytes:.2f} % of the weight bytes)")
+        print(f"  compensated: {res['compensated']:.1f} us per step, {res['compensated'] / ngemv:.2f} us per GEMV "
+              f"(link {rbytes / res['compensated'] / 1e3:.1f} GB/s)")
+        print(f"  base only  : {res['base']:.1f} us per step, {res['base'] / ngemv:.2f} us per GEMV "
+              f"(HBM {wbytes / res['base'] / 1e3:.0f} GB/s); compensation adds "
+              f"{100 * (res['compensated'] / res['base'] - 1):.1f} %", flush=True)
+        ws.close()
+        del layers, xpool
 
 
 def ksweep(args):
@@ -327,7 +418,7 @@ def tune(args):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select", "rformats", "tune"))
+    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select", "rformats", "configs", "tune"))
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=12)
@@ -338,7 +429,7 @@ def main():
         print("needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "tune": tune}[args.what](args)
+    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "configs": configs, "tune": tune}[args.what](args)
     return 0
 
 
