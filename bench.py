@@ -170,6 +170,15 @@ def main() -> int:
     prof_base = ws.read_profile()
     ws.set_profiling(0)
 
+    if args.pmc_calibrate:
+        # A plain elementwise kernel of known size: reads 256 MiB, writes 256 MiB.  The ratio of its
+        # FETCH_SIZE / WRITE_SIZE readings to those sizes scales the counters of the other kernels.
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            b = a + 1
+        torch.cuda.synchronize()
+        del a, b
+
     lin0 = layers[0]
     gemv_bytes = sum(lin0[name].weight_bytes() for name, _, _, _ in shapes)       # per step
     fetch_bytes = sum(lin0[name].residual_bytes(kk[name]) for name, _, _, _ in shapes)

@@ -82,6 +82,8 @@ def gemv(args):
 
 def fetch(args):
     ws = B.Workspace(28672, 28672, 4096)
+    ws.set_mode(B.MODE_SERIAL)        # separate kernels, so that the fetch kernel's own duration is reported
+    ws.set_separate_select(True)
     cases = [(4096, 1024, 81), (4096, 4096, 81), (4096, 6144, 81), (4096, 14336, 81), (14336, 4096, 286),
              (4096, 28672, 81), (4096, 4096, 512), (8192, 28672, 81), (28672, 8192, 286)]
     print("residual fetch kernel (fp16 rows, zero-copy): us / GB/s per row split (0 = built-in choice)")
@@ -119,7 +121,7 @@ def rformats(args):
     ws.set_separate_select(True)
     fmts = [("2-bit", B.R_INT2_SYM_COL, 2, 2.0), ("4-bit", B.R_INT4_SYM_COL, 4, 1.0),
             ("8-bit", B.R_INT8_SYM_COL, 8, 0.5), ("fp16", B.R_FP16, 16, 0.25)]
-    print("fetch kernel at equal link bytes: us / GB/s (rows + scales) per residual format")
+    print("fetch kernel at equal link bytes: us / GB/s over the link (rows) per residual format")
     print(f"{'K':>6s} {'N':>6s} {'k_chunk(4b)':>11s} {'MB':>6s}  " + "  ".join(f"{f[0]:>14s}" for f in fmts))
     for K, N in ((4096, 4096), (4096, 14336), (14336, 4096)):
         rows = {}
@@ -148,7 +150,7 @@ def rformats(args):
                 ms, n = ws.read_profile()["fetch"]
                 ws.set_profiling(0)
                 us = ms * 1e3 / n
-                nbytes = k * N * bits / 8 + (0 if bits == 16 else 2 * N)
+                nbytes = k * N * bits / 8
                 line += f"  {us:7.1f} / {nbytes / us / 1e3:4.1f}"
             print(line, flush=True)
         del rows
