@@ -19,21 +19,29 @@ struct AccJobs {
     int n;
 };
 
-__global__ __launch_bounds__(256) void accumulate_kernel(const AccJobs jobs, const float* __restrict__ gpart,
+// One workgroup = 64 columns x 8 wavefronts.  Wavefront p adds the partial rows s = p, p + 8, ... of both
+// producers (all its loads are independent and issued together), the eight part sums are combined as a
+// fixed tree: y = ((v0 + v1) + (v2 + v3)) + ((v4 + v5) + (v6 + v7)),  v_p = o_b,p + o_dec,p.
+__global__ __launch_bounds__(512) void accumulate_kernel(const AccJobs jobs, const float* __restrict__ gpart,
                                                         int gslices, const float* __restrict__ cpart, int cslices,
                                                         int Ntot) {
-    const int c = blockIdx.x * 256 + threadIdx.x;  // concatenated column
-    if (c >= Ntot) return;
-    float ob = 0.f;
+    __shared__ float part[8][64];
+    const int lane = threadIdx.x & 63, p = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;  // concatenated column; Ntot is a multiple of 64
+    float ob = 0.f, odec = 0.f;
 #pragma unroll 8
-    for (int s = 0; s < gslices; ++s) ob += gpart[(size_t)s * Ntot + c];
-    float odec = 0.f;
+    for (int s = p; s < gslices; s += 8) ob += gpart[(size_t)s * Ntot + c];
 #pragma unroll 8
-    for (int r = 0; r < cslices; ++r) odec += cpart[(size_t)r * Ntot + c];
+    for (int r = p; r < cslices; r += 8) odec += cpart[(size_t)r * Ntot + c];
+    part[p][lane] = ob + odec;
+    __syncthreads();
+    if (p != 0) return;
+    const float v = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) +
+                    ((part[4][lane] + part[5][lane]) + (part[6][lane] + part[7][lane]));
     int m = 0;
 #pragma unroll
     for (int i = 1; i < kMaxMulti; ++i) m += (i < jobs.n && c >= jobs.col0[i]) ? 1 : 0;
-    jobs.y[m][c - jobs.col0[m]] = (_Float16)(ob + odec);
+    jobs.y[m][c - jobs.col0[m]] = (_Float16)v;
 }
 
 __global__ __launch_bounds__(256) void clear_u32_kernel(unsigned* p, int n) {
@@ -58,7 +66,7 @@ hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* 
     }
     jobs.col0[sh.n] = sh.col0[sh.n];
     const int Ntot = sh.col0[sh.n];
-    return launch_kernel(tm, accumulate_kernel, dim3((Ntot + 255) / 256), dim3(256), 0, stream, jobs, gpart, gslices,
+    return launch_kernel(tm, accumulate_kernel, dim3(Ntot / 64), dim3(512), 0, stream, jobs, gpart, gslices,
                          cpart, cslices, Ntot);
 }
 

@@ -54,12 +54,16 @@ __device__ __forceinline__ float load_partial(const float* p) {
 // All 64 lanes: add the partial rows of tile nt of matrix m, write y, reset the counter.
 __device__ __forceinline__ void finalize_tile(const FinalizeArgs& fa, int m, int nt, int lane) {
     const int cc = fa.col0[m] + nt * 64 + lane;
-    float ob = 0.f, odec = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < fa.gslices; ++s) ob += load_partial(fa.gpart + (size_t)s * fa.Ntot + cc);
-#pragma unroll 8
-    for (int r = 0; r < fa.cslices; ++r) odec += load_partial(fa.cpart + (size_t)r * fa.Ntot + cc);
-    fa.y[m][nt * 64 + lane] = (_Float16)(ob + odec);
+    // The summation order of accumulate_kernel: eight interleaved part sums, combined as a fixed tree.
+    float v[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        float ob = 0.f, odec = 0.f;
+        for (int s = p; s < fa.gslices; s += 8) ob += load_partial(fa.gpart + (size_t)s * fa.Ntot + cc);
+        for (int r = p; r < fa.cslices; r += 8) odec += load_partial(fa.cpart + (size_t)r * fa.Ntot + cc);
+        v[p] = ob + odec;
+    }
+    fa.y[m][nt * 64 + lane] = (_Float16)(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
     if (lane == 0) fa.counters[fa.tile0[m] + nt] = 0;  // ready for the next call (stream-ordered after this one)
 }
 
