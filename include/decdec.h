@@ -222,7 +222,17 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  * By default the base GEMV and steps 1-3 run side by side inside one kernel on
  * `stream` (see decdec_ws_set_mode); the sum is formed on `stream` after both
  * (fp32 accumulation throughout, one rounding to fp16).  k == 0 equals the
- * plain quantised GEMV. */
+ * plain quantised GEMV.
+ * The call only enqueues kernels (plus, in TWO_STREAMS mode, event records and
+ * waits on the workspace's second stream), so it may be captured into a HIP
+ * graph; the first call that sees a given R_pinned queries the pointer's
+ * attributes, so call once (or decdec_check_pinned) before capturing.  Calls
+ * that share a workspace must be ordered on one stream: they share its
+ * partial-row and selection buffers.
+ * Errors: DECDEC_EINVAL for null / out-of-range arguments, DECDEC_EUNSUPPORTED
+ * for a format combination that is not built, DECDEC_ENOTPINNED if R_pinned
+ * is not device-accessible host memory, DECDEC_EHIP for a failed launch
+ * (decdec_last_hip_error); nothing is enqueued when validation fails. */
 int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
                 const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
                 const void* R_pinned, const void* R_scales_f16_dev,

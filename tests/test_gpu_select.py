@@ -39,6 +39,10 @@ def cases():
     big[[3, 77]] = np.inf
     big[100] = -np.inf
     yield "infinities", big
+    nans = g.standard_normal(1024).astype(np.float16)
+    nans.view(np.uint16)[[5, 600]] = [0x7E00, 0xFC01]      # quiet and signalling patterns: keys above infinity
+    nans[7] = np.inf
+    yield "nans", nans
 
 
 @pytest.mark.parametrize("name,x", list(cases()), ids=[c[0] for c in cases()])
