@@ -3,18 +3,24 @@
 // stand-alone selection kernel and by kernels that select for themselves.
 //
 // Radix select, nothing is sorted, x is read once and stays in registers:
-//   * thread t owns the 8-key chunks t, t + THREADS, t + 2*THREADS, ... of x
-//     (one 128-bit load each, at most NCH of them);
+//   * wavefront w owns the 64*NCH consecutive 8-key chunks starting at
+//     w*64*NCH; lane l holds chunk w*64*NCH + j*64 + l for j = 0..NCH-1 (one
+//     coalesced 128-bit load per j), so inside a wavefront the channel order
+//     is (j, lane, position in the chunk) and wavefronts follow one another;
 //   * the order of |x| is the order of the 15-bit key (fp16 bits, sign
-//     cleared); an LDS histogram over the high 8 key bits, scanned by one
-//     wavefront, finds the bin holding the k-th largest key; a second
-//     histogram over the low 7 bits of the keys in that bin finds the key T
-//     itself and how many keys equal to T are still needed;
-//   * every thread counts, per chunk, its keys > T and == T; wave prefix sums
-//     (DPP) plus per-wave totals in LDS give each chunk the number of such
-//     keys at lower indices, hence each selected element its output position:
-//     keys > T all go out, keys == T only the first `need` in index order.
-//     Output is in ascending index order.
+//     cleared); an LDS histogram over the high 8 key bits finds the bin
+//     holding the k-th largest key (kHistCopies copies picked by lane would
+//     spread atomics that collide on few bins; measured, one copy is fastest); a
+//     second histogram over the low 7 bits of the keys in that bin finds the
+//     key T itself and how many keys equal to T are still needed.  Every
+//     wavefront scans the histograms for itself (DPP prefix sum + readlane),
+//     which saves the barriers a single scanning wavefront would need;
+//   * per round j every thread counts its keys > T and == T; a wave prefix
+//     sum per round, the round totals (readlane) and per-wave totals in LDS
+//     give each thread the number of such keys at lower indices, hence each
+//     selected element its output position: keys > T all go out, keys == T
+//     only the first `need` in index order.  Only marked keys are visited when
+//     writing.  Output is in ascending index order.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -23,12 +29,12 @@
 namespace decdec {
 
 constexpr int kSelectMaxChunks = 8;  // 8-key chunks per thread at most
+constexpr int kHistCopies = 1;
 
 struct SelectShared {
-    unsigned hist1[256];
+    unsigned hist1[kHistCopies][256];
     unsigned hist2[128];
-    unsigned wtot[kSelectMaxChunks][16];  // per chunk round and wave: (keys > T) | (keys == T) << 16
-    unsigned bin[2], rem[2];
+    unsigned wtot[16];  // per wave: (keys > T) | (keys == T) << 16
 };
 
 template <int CTRL, int ROW_MASK, bool BOUND_CTRL>
@@ -47,29 +53,39 @@ __device__ __forceinline__ unsigned wave_incl_scan(unsigned v) {
     return v;
 }
 
-// Run by one wavefront.  hist holds NB = 64*PER bins in ascending key order and
-// at least kk >= 1 keys in total.  Finds the bin b with fewer than kk keys in
-// the bins above it and at least kk in the bins >= b; stores b and
-// kk - (#keys above b).
-template <int PER>
-__device__ __forceinline__ void wave_find_bin(const unsigned* hist, unsigned kk, unsigned* out_bin,
-                                              unsigned* out_rem, int lane) {
+// Run by all 64 lanes of a wavefront.  hist holds COPIES histograms of
+// NB = 64*PER bins in ascending key order whose sum has at least kk >= 1 keys.
+// Finds the bin b with fewer than kk keys in the bins above it and at least kk
+// in the bins >= b; returns b and kk - (#keys above b) in every lane.
+template <int PER, int COPIES>
+__device__ __forceinline__ void wave_find_bin(const unsigned* hist, unsigned kk, unsigned& bin, unsigned& rem,
+                                              int lane) {
     constexpr int NB = 64 * PER;
     unsigned c[PER], tot = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        c[j] = hist[NB - 1 - (lane * PER + j)];  // descending key order
+        const int b = NB - 1 - (lane * PER + j);  // descending key order
+        c[j] = 0;
+#pragma unroll
+        for (int r = 0; r < COPIES; ++r) c[j] += hist[r * NB + b];
         tot += c[j];
     }
     unsigned above = wave_incl_scan(tot) - tot;  // keys in bins above this lane's bins
+    unsigned b_l = 0, r_l = 1;
+    bool found = false;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
         if (above < kk && kk <= above + c[j]) {
-            *out_bin = (unsigned)(NB - 1 - (lane * PER + j));
-            *out_rem = kk - above;
+            b_l = (unsigned)(NB - 1 - (lane * PER + j));
+            r_l = kk - above;
+            found = true;
         }
         above += c[j];
     }
+    const unsigned long long mask = __ballot(found);  // exactly one lane unless the histogram is short of kk keys
+    const int src = mask ? __builtin_ctzll(mask) : 0;
+    bin = (unsigned)__builtin_amdgcn_readlane((int)b_l, src);
+    rem = (unsigned)__builtin_amdgcn_readlane((int)r_l, src);
 }
 
 __device__ __forceinline__ unsigned key_of(const uint4& c, int e) {
@@ -91,39 +107,33 @@ __device__ __forceinline__ void block_select_topk(const uint16_t* __restrict__ x
     static_assert(THREADS % 64 == 0 && THREADS / 64 <= 16 && NCH <= kSelectMaxChunks, "select shape");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunks = K / 8;
+    const int c0 = wave * 64 * NCH + lane;  // this thread's chunk of round j is c0 + 64*j
     const uint4* x128 = reinterpret_cast<const uint4*>(x);
 
     uint4 ch[NCH];
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-        const int c = tid + j * THREADS;
-        ch[j] = c < nchunks ? x128[c] : make_uint4(0, 0, 0, 0);
-    }
-    for (int i = tid; i < 256; i += THREADS) sh.hist1[i] = 0;
+    for (int j = 0; j < NCH; ++j) ch[j] = c0 + 64 * j < nchunks ? x128[c0 + 64 * j] : make_uint4(0, 0, 0, 0);
+    for (int i = tid; i < kHistCopies * 256; i += THREADS) (&sh.hist1[0][0])[i] = 0;
     for (int i = tid; i < 128; i += THREADS) sh.hist2[i] = 0;
-    if (tid < 2) {
-        sh.bin[tid] = 0;
-        sh.rem[tid] = 1;
-    }
     __syncthreads();
 
     // pass 1: high 8 bits of the key
+    unsigned* h1 = sh.hist1[lane & (kHistCopies - 1)];
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-        if (tid + j * THREADS < nchunks) {
+        if (c0 + 64 * j < nchunks) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) atomicAdd(&sh.hist1[key_of(ch[j], e) >> 7], 1u);
+            for (int e = 0; e < 8; ++e) atomicAdd(&h1[key_of(ch[j], e) >> 7], 1u);
         }
     }
     __syncthreads();
-    if (wave == 0) wave_find_bin<4>(sh.hist1, (unsigned)k, &sh.bin[0], &sh.rem[0], lane);
-    __syncthreads();
-    const unsigned b1 = sh.bin[0];
+    unsigned b1, rem1;
+    wave_find_bin<4, kHistCopies>(&sh.hist1[0][0], (unsigned)k, b1, rem1, lane);
 
     // pass 2: low 7 bits of the keys inside bin b1
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-        if (tid + j * THREADS < nchunks) {
+        if (c0 + 64 * j < nchunks) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const unsigned key = key_of(ch[j], e);
@@ -132,61 +142,58 @@ __device__ __forceinline__ void block_select_topk(const uint16_t* __restrict__ x
         }
     }
     __syncthreads();
-    if (wave == 0) wave_find_bin<2>(sh.hist2, sh.rem[0], &sh.bin[1], &sh.rem[1], lane);
-    __syncthreads();
-    const unsigned T = (b1 << 7) | sh.bin[1];
-    const unsigned need = sh.rem[1];  // keys equal to T still to take (>= 1)
+    unsigned b2, need;  // need: keys equal to T still to take (>= 1)
+    wave_find_bin<2, 1>(sh.hist2, rem1, b2, need, lane);
+    const unsigned T = (b1 << 7) | b2;
 
-    // compaction in index order: chunk c = tid + j*THREADS precedes c' > c
-    unsigned cnt[NCH], incl[NCH];
+    // compaction in index order.  Per round: bit e of gtm[j] / eqm[j] = key e of the chunk is > T / == T;
+    // counts are packed as (> T) | (== T) << 16 (at most 4096 each per wavefront: no carry between the halves).
+    unsigned gtm[NCH], eqm[NCH], excl[NCH];  // excl: this wave's marked keys at lower indices (earlier rounds, lower lanes)
+    unsigned wave_cnt = 0;                    // uniform: marked keys of the rounds so far
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-        unsigned gt = 0, eq = 0;
-        if (tid + j * THREADS < nchunks) {
+        unsigned g = 0, q = 0;
+        if (c0 + 64 * j < nchunks) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const unsigned key = key_of(ch[j], e);
-                gt += key > T;
-                eq += key == T;
+                g |= (unsigned)(key > T) << e;
+                q |= (unsigned)(key == T) << e;
             }
         }
-        cnt[j] = gt | (eq << 16);           // both counts <= 8 per chunk, <= 512 per wave: no carry between halves
-        incl[j] = wave_incl_scan(cnt[j]);
-        if (lane == 63) sh.wtot[j][wave] = incl[j];
+        gtm[j] = g;
+        eqm[j] = q;
+        const unsigned cnt = (unsigned)__builtin_popcount(g) | ((unsigned)__builtin_popcount(q) << 16);
+        const unsigned incl = wave_incl_scan(cnt);
+        excl[j] = wave_cnt + incl - cnt;
+        wave_cnt += (unsigned)__builtin_amdgcn_readlane((int)incl, 63);
     }
+    if (lane == 0) sh.wtot[wave] = wave_cnt;
     __syncthreads();
-    unsigned run_gt = 0, run_eq = 0;  // keys > T / == T in all chunks before round j
+    unsigned base_gt = 0, base_eq = 0;  // marked keys of the wavefronts before this one
+#pragma unroll
+    for (int w = 0; w < THREADS / 64; ++w) {
+        const unsigned t = sh.wtot[w];
+        base_gt += w < wave ? (t & 0xFFFFu) : 0u;
+        base_eq += w < wave ? (t >> 16) : 0u;
+    }
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-        if (j * THREADS >= nchunks) break;
-        unsigned before = incl[j] - cnt[j];
-        unsigned round_tot = 0;
-        for (int w = 0; w < THREADS / 64; ++w) {
-            const unsigned t = sh.wtot[j][w];
-            before += w < wave ? t : 0u;
-            round_tot += t;
-        }
-        unsigned pos_gt = run_gt + (before & 0xFFFFu), seen_eq = run_eq + (before >> 16);
-        run_gt += round_tot & 0xFFFFu;
-        run_eq += round_tot >> 16;
-        const int c = tid + j * THREADS;
-        if (c < nchunks && cnt[j] != 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned key = key_of(ch[j], e);
-                int pos = -1;
-                if (key > T) {
-                    pos = (int)(pos_gt + min(seen_eq, need));
-                    ++pos_gt;
-                } else if (key == T) {
-                    if (seen_eq < need) pos = (int)(pos_gt + seen_eq);
-                    ++seen_eq;
-                }
-                if (pos >= 0 && pos < k) {  // pos < k always holds; the bound keeps a logic error from writing outside
-                    idx_out[pos] = c * 8 + e;
-                    if (xsel_out) xsel_out[pos] = raw_of(ch[j], e);
-                }
+        unsigned m = gtm[j] | eqm[j];
+        if (m == 0) continue;  // most threads: a chunk holds 8 keys, of which k/K are selected
+        unsigned pos_gt = base_gt + (excl[j] & 0xFFFFu), seen_eq = base_eq + (excl[j] >> 16);
+        while (m) {
+            const int e = __builtin_ctz(m);
+            m &= m - 1;
+            const bool is_gt = (gtm[j] >> e) & 1u;
+            const unsigned pos = pos_gt + min(seen_eq, need);
+            // pos < k always holds for a taken key; the bound keeps a logic error from writing outside
+            if ((is_gt || seen_eq < need) && pos < (unsigned)k) {
+                idx_out[pos] = (c0 + 64 * j) * 8 + e;
+                if (xsel_out) xsel_out[pos] = raw_of(ch[j], e);
             }
+            pos_gt += is_gt;
+            seen_eq += !is_gt;
         }
     }
 }
