@@ -133,3 +133,50 @@ def test_llama3_8b_gate_up_integer_residuals_sampled(ws, bits, rfmt):
         assert np.all(np.isfinite(yh))
         err = oracle.error_metric(yh[cols], y_ref, rms=float(np.sqrt(np.mean(y_ref ** 2))))
         assert err <= TOL_Y, err
+
+
+@pytest.mark.timeout(600)
+def test_config5_selection_every_step_every_layer():
+    """Config 5: 64 steps x 32 layers x the four distinct inputs of a layer (8192 activation vectors,
+    Student-t with 0.5 % outlier channels x 30 redrawn each step), k_chunk = 15: the indices of every
+    selection equal the oracle's."""
+    checked = 0
+    bufs = {K: (torch.empty(K, dtype=torch.float16, device="cuda"),
+                torch.empty(workloads.k_for_kchunk(K, 15), dtype=torch.int32, device="cuda")) for K in (4096, 14336)}
+    for step in range(64):
+        for layer in range(32):
+            for which, K in (("attn_in", 4096), ("o_in", 4096), ("mlp_in", 4096), ("down_in", 14336)):
+                k = workloads.k_for_kchunk(K, 15)
+                x = workloads.x_student_t(5, layer, which, step, K, outlier_frac=0.005, outlier_mult=30.0)
+                xd, idx = bufs[K]
+                xd.copy_(torch.from_numpy(x))
+                dd.decdec_select_topk(xd, K, k, idx, None)
+                got = idx.cpu().numpy()
+                assert np.array_equal(got, oracle.topk_abs(x, k)), (step, layer, which)
+                checked += 1
+    assert checked == 8192
+
+
+@pytest.mark.timeout(600)
+def test_config5_layer_all_gemvs_int4_residuals(ws):
+    """Config 5, layer 0, one step: the seven GEMVs as the four grouped calls the benchmark issues,
+    3-bit weights, 4-bit residuals (oracle quantiser on a two-point scale grid to keep the test short),
+    every output checked."""
+    order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
+    shape = {name: (K, N) for name, K, N, _ in workloads.LLAMA3_8B_LAYER}
+    for which, names in order:
+        K = shape[names[0]][0]
+        k = workloads.k_for_kchunk(K, 15)
+        x = workloads.x_student_t(5, 0, which, 0, K, outlier_frac=0.005, outlier_mult=30.0)
+        probs = [Problem(workloads.weights(5, 0, n, *shape[n]), 3, rfmt="int4", alphas=np.array([0.8, 1.0]),
+                         keep_dense=True) for n in names]
+        ys = [torch.full((p.N,), float("nan"), dtype=torch.float16, device="cuda") for p in probs]
+        lin = dd.make_linears([(p.desc, p.device()["Wq"], p.device()["scales"], p.device()["zl"], p.device()["R"],
+                                p.device()["Rs"], y) for p, y in zip(probs, ys)])
+        dd.decdec_gemv_multi(lin, torch.from_numpy(x).cuda(), k, ws)
+        torch.cuda.synchronize()
+        idx = ws.read_selection(k)[0]
+        for n, p, y in zip(names, probs, ys):
+            y_ref, sc = p.reference(x, k)
+            assert_parity(y.cpu().numpy(), y_ref, idx, sc, what=f"config 5 {n}")
+        del probs, lin
