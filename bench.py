@@ -34,7 +34,7 @@ LINK_PEAK_GBS = 64.0        # PCIe Gen5 x16, one direction (the box reports 32 G
 # of the default workload.  Only valid for that workload; other settings report null.
 PMC_TRAFFIC_BYTES_PER_STEP = 89.08e6 + 1.25e6
 K_FRACTION = 0.02
-CFG = 2                     # BASELINE config index used for seeding (configs[1])
+CFG = 2                     # workload index used for seeding (the second of the five workloads: one Llama-3-8B-shaped layer)
 
 
 def main() -> int:

@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the BASELINE configs, in the launch
+"""GPU parity at the full sizes of the benchmark workloads, in the launch
 configuration bench.py times.  Llama-3-8B shapes: the oracle quantises and
 checks every output.  Llama-3-70B shapes (235 M weights): stored parameters
 are drawn directly (random codes, a random ascending codebook per column, small

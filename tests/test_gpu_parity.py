@@ -20,7 +20,7 @@ def ws():
 
 
 def test_config1_4bit_k32(ws):
-    """BASELINE config 1: 1024x1024, 4-bit group 128, 10 outlier channels x20, k = 32."""
+    """Workload 1: 1024x1024, 4-bit group 128, 10 outlier channels x20, k = 32."""
     c = workloads.config1()
     p = Problem(c["W"], 4)
     y_ref, sc = p.reference(c["x"], c["k"])
