@@ -34,6 +34,7 @@ LINK_PEAK_GBS = 64.0        # PCIe Gen5 x16, one direction (the box reports 32 G
 # of the default workload.  Only valid for that workload; other settings report null.
 PMC_TRAFFIC_BYTES_PER_STEP = 89.08e6 + 1.25e6
 K_FRACTION = 0.02
+K_SWEEP = (0.001, 0.005, 0.01, 0.05)   # further fractions of K timed for the latency-vs-k list
 CFG = 2                     # workload index used for seeding (the second of the five workloads: one Llama-3-8B-shaped layer)
 
 
@@ -93,7 +94,7 @@ def main() -> int:
     kk = {name: workloads.k_for_fraction(K, K_FRACTION) for name, K, _, _ in shapes}
     maxK = max(K for _, K, _, _ in shapes)
     maxN = 2 * max(N for _, _, N, _ in shapes)       # room for the concatenated columns of gate + up
-    ws = dd.Workspace(maxK, maxN, max(kk.values()))
+    ws = dd.Workspace(maxK, maxN, max(max(kk.values()), workloads.k_for_fraction(maxK, max(K_SWEEP))))
     if args.fetch_split:
         ws.set_fetch_split(args.fetch_split)
     if args.inkernel_accumulate:
@@ -109,16 +110,25 @@ def main() -> int:
               for lins in layers]
     n_calls = len(order)
 
-    def step(i: int, compensate: bool = True):
+    Kof = {name: K for name, K, _, _ in shapes}
+
+    def step(i: int, compensate=True):
+        """compensate: True = the workload's k (2 %), False = base GEMV only, a float = that fraction of K."""
         xs = xpool[i % args.xpool]
         for (which, names), grp in zip(order, groups[i % args.layers]):
-            grp.gemv(xs[which], kk[names[0]] if compensate else 0, ws)
+            if compensate is True:
+                k = kk[names[0]]
+            elif compensate is False:
+                k = 0
+            else:
+                k = workloads.k_for_fraction(Kof[names[0]], compensate)
+            grp.gemv(xs[which], k, ws)
 
     graphs = {}
     cap_stream = torch.cuda.Stream() if args.graph else None
     gs = max(1, args.graph_steps) if args.graph else 1
 
-    def run_steps(i0: int, n: int, compensate: bool):
+    def run_steps(i0: int, n: int, compensate):
         """Steps i0 .. i0+n-1, eagerly or as replays of captured graphs of `gs` consecutive steps each
         (a tail shorter than gs runs eagerly)."""
         import math
@@ -139,7 +149,7 @@ def main() -> int:
                 step(i, compensate)
                 i += 1
 
-    def timed(n: int, compensate: bool) -> float:
+    def timed(n: int, compensate) -> float:
         if args.graph:
             run_steps(0, n, compensate)          # capture outside the timed region
         torch.cuda.synchronize()
@@ -153,6 +163,21 @@ def main() -> int:
     ms_step = timed(args.steps, True)
     run_steps(0, args.warmup, False)
     ms_base = timed(args.steps, False)
+
+    # latency against k (the metric is quoted "vs k"): the same steps at other fractions of K
+    vs_k = [{"k_frac": 0.0, "us_per_gemv": round(ms_base * 1e3 / len(shapes), 3), "residual_MB_per_step": 0.0}]
+    for frac in sorted(set(K_SWEEP) | {K_FRACTION}):
+        if frac == K_FRACTION:
+            ms = ms_step
+        else:
+            run_steps(0, min(args.warmup, gs), frac)
+            ms = timed(args.steps, frac)
+            for key in [key for key in graphs if key[1] == frac]:
+                del graphs[key]
+        rb = sum(workloads.k_for_fraction(K, frac) * N * 2 for _, K, N, _ in shapes)
+        vs_k.append({"k_frac": frac, "us_per_gemv": round(ms * 1e3 / len(shapes), 3),
+                     "residual_MB_per_step": round(rb / 1e6, 3),
+                     "link_GBs_whole_step": round(rb / (ms * 1e-3) / 1e9, 2)})
 
     # spread: the same compensated steps once more, each graph replay (gs steps) timed on its own
     spread = []
@@ -243,6 +268,7 @@ def main() -> int:
             "algorithmic_bytes_per_launch": round(fetch_bytes / n_calls),
             "avg_launch_us": round(f_ms * 1e3 / max(f_n, 1), 3),
         },
+        "vs_k": vs_k,
         "select_avg_us": round(s_ms * 1e3 / max(s_n, 1), 3),
         "accumulate_avg_us": round(prof["accumulate"][0] * 1e3 / max(prof["accumulate"][1], 1), 3),
         "setup_s": round(setup_s, 1),
