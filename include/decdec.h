@@ -45,7 +45,7 @@ typedef enum {
     DECDEC_OK = 0,
     DECDEC_EINVAL = -1,       /* null pointer, size or k out of range, bad alignment */
     DECDEC_EUNSUPPORTED = -2, /* format / bit-width combination not implemented */
-    DECDEC_ENOTPINNED = -3,   /* residual pointer is not GPU-visible host memory */
+    DECDEC_ENOTPINNED = -3,   /* residual pointer is neither pinned host memory nor device memory */
     DECDEC_EHIP = -4,         /* a HIP runtime call failed; see decdec_last_hip_error */
     DECDEC_ENOMEM = -5        /* workspace allocation failed */
 } decdec_status;
@@ -215,7 +215,10 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  *   Wq_dev         dev, packed by decdec_pack_weights (or decdec_quantize_uniform)
  *   scales_f16_dev dev fp16 [K/128][N]           (UNIFORM; ignored for LUT)
  *   zeros_or_lut   dev fp16 [K/128][N] zero points (UNIFORM) or fp16 [N][8] (LUT)
- *   R_pinned       pinned fp16 [K][N] or integer codes [K][N*bits/8]; may be NULL if k == 0
+ *   R_pinned       fp16 [K][N] or integer codes [K][N*bits/8] in pinned host memory, read in
+ *                  place over the host link (the paper's placement, Section 4.3), or in
+ *                  device memory (a GPU with room for the residuals: the same kernels
+ *                  then read the selected rows from HBM); may be NULL if k == 0
  *   R_scales_f16_dev dev fp16 [N] (integer residual formats only, else NULL)
  *   k              salient channels, 0 <= k <= min(K, maxk of ws)
  *   y_f16_dev      dev fp16 [N] out
@@ -231,7 +234,7 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  * partial-row and selection buffers.
  * Errors: DECDEC_EINVAL for null / out-of-range arguments, DECDEC_EUNSUPPORTED
  * for a format combination that is not built, DECDEC_ENOTPINNED if R_pinned
- * is not device-accessible host memory, DECDEC_EHIP for a failed launch
+ * is neither pinned host memory nor device memory, DECDEC_EHIP for a failed launch
  * (decdec_last_hip_error); nothing is enqueued when validation fails. */
 int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
                 const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
@@ -308,6 +311,8 @@ const char* decdec_strerror(int status);
 int decdec_last_hip_error(void); /* hipError_t of the last failing HIP call on this thread */
 /* DECDEC_OK if p is GPU-visible host memory, DECDEC_ENOTPINNED otherwise. */
 int decdec_check_pinned(const void* p);
+/* DECDEC_OK if p may serve as a residual pointer: pinned host memory or device memory. */
+int decdec_check_residual_pointer(const void* p);
 
 #ifdef __cplusplus
 }

@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = (
     "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_pack_residual_int", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
-    "decdec_quantize_uniform", "decdec_residual_f32", "decdec_quantize_residual", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned",
+    "decdec_quantize_uniform", "decdec_residual_f32", "decdec_quantize_residual", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned", "decdec_check_residual_pointer",
 )
 
 
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
     L.decdec_sc_buffer_bytes.restype = sz
     L.decdec_sc_buffer_bytes.argtypes = [i32]
     L.decdec_check_pinned.argtypes = [vp]
+    L.decdec_check_residual_pointer.argtypes = [vp]
     L.decdec_ws_create.argtypes = [i32, i32, i32, C.POINTER(vp)]
     L.decdec_ws_destroy.argtypes = [vp]
     L.decdec_ws_last_selection.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
@@ -133,6 +134,10 @@ def decdec_sc_buffer_bytes(k: int) -> int:
 
 def decdec_check_pinned(t) -> int:
     return int(lib().decdec_check_pinned(_ptr(t)))
+
+
+def decdec_check_residual_pointer(t) -> int:
+    return int(lib().decdec_check_residual_pointer(_ptr(t)))
 
 
 class Workspace:

@@ -70,6 +70,7 @@ struct decdec_ws {
     int32_t inkernel_accumulate;  // 1: the last producer of a tile adds the partial rows (no accumulate kernel)
     int32_t counters_dirty;       // a call failed half-way: clear the counters before the next one
     const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
+    uint8_t pinned_dev[kPinnedCache];     // 1: that pointer is device memory
     int pinned_n, pinned_next;
     // optional kernel timing: per call one (start, stop) event pair per kernel class
     hipEvent_t* prof_ev;   // [prof_cap][kProfEvents]: gemv, select, fetch, accumulate
@@ -95,16 +96,26 @@ int decdec_last_hip_error(void) { return g_last_hip_error; }
 
 size_t decdec_sc_buffer_bytes(int32_t k) { return k > 0 ? (size_t)k * (4 + 2) : 0; }
 
-int decdec_check_pinned(const void* p) {
-    if (p == nullptr) return DECDEC_EINVAL;
+// hipMemoryTypeHost / hipMemoryTypeDevice, or -1 for memory the GPU cannot read.
+static int residual_memory_type(const void* p) {
     hipPointerAttribute_t at;
     std::memset(&at, 0, sizeof(at));
     const hipError_t e = hipPointerGetAttributes(&at, p);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        return DECDEC_ENOTPINNED;
+        return -1;
     }
-    return at.type == hipMemoryTypeHost ? DECDEC_OK : DECDEC_ENOTPINNED;
+    return at.type == hipMemoryTypeHost || at.type == hipMemoryTypeDevice ? (int)at.type : -1;
+}
+
+int decdec_check_pinned(const void* p) {
+    if (p == nullptr) return DECDEC_EINVAL;
+    return residual_memory_type(p) == (int)hipMemoryTypeHost ? DECDEC_OK : DECDEC_ENOTPINNED;
+}
+
+int decdec_check_residual_pointer(const void* p) {
+    if (p == nullptr) return DECDEC_EINVAL;
+    return residual_memory_type(p) >= 0 ? DECDEC_OK : DECDEC_ENOTPINNED;
 }
 
 int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) {
@@ -378,12 +389,19 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
     return DECDEC_OK;
 }
 
-static int check_pinned_cached(decdec_ws* ws, const void* R_pinned) {
-    for (int i = 0; i < ws->pinned_n; ++i)
-        if (ws->pinned_ok[i] == R_pinned) return DECDEC_OK;
-    const int prc = decdec_check_pinned(R_pinned);
-    if (prc != DECDEC_OK) return prc;
+// *in_device: the residuals live in device memory (not over the host link).
+static int check_pinned_cached(decdec_ws* ws, const void* R_pinned, bool* in_device) {
+    for (int i = 0; i < ws->pinned_n; ++i) {
+        if (ws->pinned_ok[i] == R_pinned) {
+            *in_device = ws->pinned_dev[i] != 0;
+            return DECDEC_OK;
+        }
+    }
+    const int type = residual_memory_type(R_pinned);
+    if (type < 0) return DECDEC_ENOTPINNED;
+    *in_device = type == (int)hipMemoryTypeDevice;
     ws->pinned_ok[ws->pinned_next] = R_pinned;
+    ws->pinned_dev[ws->pinned_next] = *in_device ? 1 : 0;
     ws->pinned_next = (ws->pinned_next + 1) % kPinnedCache;
     if (ws->pinned_n < kPinnedCache) ++ws->pinned_n;
     return DECDEC_OK;
@@ -420,13 +438,16 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     }
     sh.K = d0->K;
     if (sh.K > ws->maxK || sh.col0[count] > ws->maxN || k < 0 || k > sh.K || k > ws->maxk) return DECDEC_EINVAL;
+    bool residuals_in_hbm = k > 0;  // all of them: the fetch is then bound by HBM latency, not by the host link
     if (k > 0) {
         if (have_idx && (idx_in == nullptr || xsel_in == nullptr)) return DECDEC_EINVAL;
         for (int m = 0; m < count; ++m) {
             if (lin[m].R_pinned == nullptr) return DECDEC_EINVAL;
             if (d0->rfmt != DECDEC_R_FP16 && lin[m].R_scales_f16_dev == nullptr) return DECDEC_EINVAL;
-            const int prc = check_pinned_cached(ws, lin[m].R_pinned);
+            bool in_device = false;
+            const int prc = check_pinned_cached(ws, lin[m].R_pinned, &in_device);
             if (prc != DECDEC_OK) return prc;
+            residuals_in_hbm = residuals_in_hbm && in_device;
         }
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
@@ -454,7 +475,7 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     int gpw = 1;
     const int gslices =
         gemv_slices(tiles, sh.K / kGroup, ws->gemv_gpw, fused ? kWavesPerBlock : kGemvAloneWaves, &gpw);
-    const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, ws->fetch_split) : 0;
+    const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, ws->fetch_split, residuals_in_hbm) : 0;
 
     FinalizeArgs fa{};
     int t0 = 0;

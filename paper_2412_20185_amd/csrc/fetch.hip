@@ -35,14 +35,16 @@ inline int total_wavecols(int rfmt, const MultiShape& sh) {
 
 }  // namespace
 
-int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split) {
+int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm) {
     const int wavecols = total_wavecols(rfmt, sh);
     int slices;
     if (row_split > 0) {
         slices = row_split;
     } else {
-        // about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight
-        slices = (128 + wavecols - 1) / wavecols;
+        // Host link: about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight saturate
+        // it.  Rows in device memory: latency bound, so eight times as many wavefronts.
+        const int waves = in_hbm ? 1024 : 128;
+        slices = (waves + wavecols - 1) / wavecols;
     }
     if (slices > k) slices = k;
     if (slices > kMaxFetchSlices) slices = kMaxFetchSlices;

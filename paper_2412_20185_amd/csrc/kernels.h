@@ -80,8 +80,9 @@ hipError_t launch_select_bucket(const void* x, int K, int k_chunk, float b0, flo
                                 void* xsel_out, hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // fetch.hip --------------------------------------------------------------
-// cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic).
-int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split);
+// cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic); in_hbm: the residual rows are in
+// device memory, not behind the host link.
+int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm);
 // select_chunks (from fetch_select_chunks) > 0: the kernel runs the exact top-k on x itself and writes
 // the selection to idx / xsel; 0: idx / xsel hold the selection already (x is not read).
 int fetch_select_chunks(int K, int k);

@@ -52,6 +52,14 @@ class UniformLinear:
         torch.cuda.synchronize()
         del Wd, R_dev
 
+    def residual_to_device(self):
+        """Moves the residual from pinned host memory into GPU memory (for a GPU with room for it:
+        the same kernels then read the selected rows from HBM instead of over the host link)."""
+        if self.R is not None and not self.R.is_cuda:
+            self.R = self.R.cuda()
+            torch.cuda.synchronize()
+        return self
+
     def weight_bytes(self) -> int:
         """Algorithmic bytes the base GEMV has to move: packed codes, fp16 scales
         and zero points, x and y."""

@@ -306,3 +306,29 @@ def test_large_problems_fall_back_to_the_selection_kernel(K, N, k):
     y, idx, _ = p.run(x, k, ws)
     assert_parity(y, y_ref, idx, sc, what=f"fallback select {K}x{N} k={k}")
     ws.close()
+
+
+@pytest.mark.parametrize("rfmt", ["fp16", "int4", "int8"])
+def test_residuals_resident_in_device_memory(ws, rfmt):
+    """The residual pointer may be device memory (a GPU whose memory also holds the residuals): the
+    kernels are the same, only the rows are split over more wavefronts, so y meets the same bar
+    against the oracle; memory the GPU cannot read (plain pageable host memory) is refused."""
+    K, N, k = 2048, 1536, 41
+    p = Problem(workloads.weights(95, 0, 0, K, N), 3, rfmt=rfmt, alphas=oracle.quantize.DEFAULT_ALPHAS[::10])
+    x = workloads.x_gauss_outliers(95, 0, 0, 0, K)
+    y_ref, sc = p.reference(x, k)
+    y_host, idx, _ = p.run(x, k, ws)
+    assert_parity(y_host, y_ref, idx, sc, what=f"pinned {rfmt}")
+    d = p.device()
+    pinned = d["R"]
+    assert dd.decdec_check_pinned(pinned) == 0 and dd.decdec_check_residual_pointer(pinned) == 0
+    d["R"] = pinned.cuda()
+    assert dd.decdec_check_pinned(d["R"]) == -3 and dd.decdec_check_residual_pointer(d["R"]) == 0
+    y_dev, idx2, _ = p.run(x, k, ws)
+    assert_parity(y_dev, y_ref, idx2, sc, what=f"device-resident {rfmt}")
+    d["R"] = torch.from_numpy(pinned.numpy().copy())          # pageable host memory
+    assert dd.decdec_check_residual_pointer(d["R"]) == -3
+    with pytest.raises(dd.DecdecError) as e:
+        p.run(x, k, ws)
+    assert e.value.status == -3
+    torch.cuda.synchronize()
