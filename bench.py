@@ -47,6 +47,7 @@ def main() -> int:
                     help="distinct layers rotated over (12 x 89 MB > 1 GB: weights come from HBM, not from the 256 MB L3)")
     ap.add_argument("--xpool", type=int, default=32, help="distinct activation draws rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-k-sweep", action="store_true", help="skip the latency-vs-k passes")
     ap.add_argument("--no-hbm-residuals", action="store_true",
                     help="skip the extra pass with the residuals resident in GPU memory")
     ap.add_argument("--fetch-split", type=int, default=0)
@@ -169,7 +170,7 @@ def main() -> int:
 
     # latency against k (the metric is quoted "vs k"): the same steps at other fractions of K
     vs_k = [{"k_frac": 0.0, "us_per_gemv": round(ms_base * 1e3 / len(shapes), 3), "residual_MB_per_step": 0.0}]
-    for frac in sorted(set(K_SWEEP) | {K_FRACTION}):
+    for frac in sorted((set() if args.no_k_sweep else set(K_SWEEP)) | {K_FRACTION}):
         if frac == K_FRACTION:
             ms = ms_step
         else:
