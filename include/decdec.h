@@ -219,7 +219,9 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  *                  place over the host link (the paper's placement, Section 4.3), or in
  *                  device memory (a GPU with room for the residuals: the same kernels
  *                  then read the selected rows from HBM); may be NULL if k == 0
- *   R_scales_f16_dev dev fp16 [N] (integer residual formats only, else NULL)
+ *   R_scales_f16_dev fp16 [N] (integer residual formats only, else NULL): device memory, or pinned
+ *                  host memory as in the paper (Section 4.2: all scales are fetched with the rows),
+ *                  at the price of 2 N more bytes over the host link per call
  *   k              salient channels, 0 <= k <= min(K, maxk of ws)
  *   y_f16_dev      dev fp16 [N] out
  * By default the base GEMV and steps 1-3 run side by side inside one kernel on

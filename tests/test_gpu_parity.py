@@ -332,3 +332,20 @@ def test_residuals_resident_in_device_memory(ws, rfmt):
         p.run(x, k, ws)
     assert e.value.status == -3
     torch.cuda.synchronize()
+
+
+def test_int4_scales_fetched_from_pinned_host_memory(ws):
+    """The paper keeps the column scales of the 4-bit residuals in CPU memory and fetches all of them with
+    the selected rows (Section 4.2): the scale pointer may be pinned host memory, the result is the same
+    bit for bit as with the scales in GPU memory."""
+    K, N, k = 2048, 1536, 41
+    p = Problem(workloads.weights(96, 0, 0, K, N), 3, rfmt="int4", alphas=oracle.quantize.DEFAULT_ALPHAS[::10])
+    x = workloads.x_gauss_outliers(96, 0, 0, 0, K)
+    y_ref, sc = p.reference(x, k)
+    y_dev_scales, idx, _ = p.run(x, k, ws)
+    assert_parity(y_dev_scales, y_ref, idx, sc, what="scales in GPU memory")
+    d = p.device()
+    d["Rs"] = torch.from_numpy(p.Rs).pin_memory()
+    y_host_scales, idx2, _ = p.run(x, k, ws)
+    assert np.array_equal(idx2, sc)
+    assert np.array_equal(y_host_scales.view(np.uint16), y_dev_scales.view(np.uint16))
