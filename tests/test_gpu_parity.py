@@ -349,3 +349,32 @@ def test_int4_scales_fetched_from_pinned_host_memory(ws):
     y_host_scales, idx2, _ = p.run(x, k, ws)
     assert np.array_equal(idx2, sc)
     assert np.array_equal(y_host_scales.view(np.uint16), y_dev_scales.view(np.uint16))
+
+
+def test_subnormal_fp16_residuals_are_not_flushed(ws):
+    """Residual entries below 2^-14 are fp16 subnormals; they must enter the sum with their value.
+    All weights are zero here, so y is the compensation alone: multiples of 2^-24 times powers of two,
+    every partial sum exact in fp32, hence equal to the oracle bit for bit (a flush would give 0)."""
+    g = np.random.default_rng(5)
+    K, N, k = 1024, 512, 32
+    p = Problem.__new__(Problem)
+    p.K, p.N, p.bits = K, N, 4
+    p.codes = np.zeros((K, N), np.uint8)
+    p.scales = np.ones((K // 128, N), np.float16)
+    p.zeros = np.zeros((K // 128, N), np.float16)
+    p.lut = None
+    p.R = (g.integers(-1000, 1001, size=(K, N)) * 2.0 ** -24).astype(np.float16)     # all subnormal (< 2^-14)
+    assert np.all(np.abs(p.R.astype(np.float64)) < 2.0 ** -14) and np.count_nonzero(p.R) > K * N // 2
+    p.R_real, p.Rq, p.Rs, p.rfmt = p.R, None, None, "fp16"
+    p.desc = dd.Desc(K, N, 4)
+    p.W_hat = np.zeros((K, N))
+    p._dev = None
+    x = np.zeros(K, np.float16)
+    pos = g.choice(K, size=k, replace=False)
+    x[pos] = (2.0 ** g.integers(8, 12, size=k)) * g.choice([-1.0, 1.0], size=k)        # 256 ... 2048
+    y_ref, sc = p.reference(x, k)
+    assert np.array_equal(np.sort(pos), sc) and np.abs(y_ref).max() > 1e-3
+    y, idx, _ = p.run(x, k, ws)
+    assert np.array_equal(idx, sc)
+    assert np.array_equal(y.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+    assert np.count_nonzero(y) > N // 2
