@@ -37,6 +37,11 @@ def test_llama3_8b_shapes_full_check(ws, name, bits):
         y, idx, _ = p.run(x, k, ws)
         err = assert_parity(y, y_ref, idx, sc, what=f"8B {name} b{bits} k={k}")
         print(f"8B {name} {K}x{N} b{bits} k={k}: rel err {err:.2e}")
+    # the same layer with its residual resident in GPU memory (rows split over more wavefronts)
+    d = p.device()
+    d["R"] = d["R"].cuda()
+    y, idx, _ = p.run(x, k, ws)
+    assert_parity(y, y_ref, idx, sc, what=f"8B {name} b{bits} k={k}, residual in GPU memory")
 
 
 def test_llama3_8b_down_int4_residuals(ws):
