@@ -6,7 +6,8 @@
  *     o = W_hat x  +  R_hat[sc_indices, :]^T x[sc_indices]
  *
  * where W_hat is the de-quantised 3/4-bit weight matrix resident in GPU
- * memory, R_hat the residual W - W_hat resident in pinned CPU memory, and
+ * memory, R_hat the residual W - W_hat resident in pinned CPU memory (the
+ * paper's placement; GPU memory is accepted too), and
  * sc_indices the k input channels with the largest |x| of THIS step
  * (DecDEC, Section 3.1 "(W_hat + R o M) x" and Section 4.1 steps 1-4).
  *
