@@ -15,7 +15,8 @@ channels), R_hat the stored residual W - W_hat kept in CPU memory, and
 sc_indices the k input channels with the largest |x| this step (the exact
 Top-K arm of Section 5.2, ties resolved toward the lower index).
 
-Pinned by tests/test_oracle_*.py against brute force with exact rationals,
+Pinned by tests/test_oracle_*.py and tests/test_paper_values.py against the
+numbers the paper prints, brute force with exact rationals,
 closed forms (weights on the quantisation grid), the k = 0 and k = K
 invariants, scaling laws and a planted-mistake check per function.
 Functions without an external pin: none ("parity unpinned" applies to nothing
