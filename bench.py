@@ -54,6 +54,7 @@ def main() -> int:
     ap.add_argument("--fetch-split", type=int, default=0)
     ap.add_argument("--inkernel-accumulate", action="store_true",
                     help="let the last producer of a tile add the partial rows instead of the accumulate kernel")
+    ap.add_argument("--gemv-split", type=int, default=0, help="groups of 128 input channels per wavefront (0 = built-in)")
     ap.add_argument("--graph", type=int, default=1, help="1: replay the steps as captured HIP graphs")
     ap.add_argument("--graph-steps", type=int, default=8,
                     help="consecutive steps captured into one graph (a decoder captures all its layers at once)")
@@ -103,6 +104,8 @@ def main() -> int:
         ws.set_fetch_split(args.fetch_split)
     if args.inkernel_accumulate:
         ws.set_inkernel_accumulate(True)
+    if args.gemv_split:
+        ws.set_gemv_split(args.gemv_split)
     setup_s = time.time() - t_setup
 
     # calls per step, in the layer's dependency order: (input name, k, [GEMV names])
