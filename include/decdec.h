@@ -27,7 +27,16 @@
  *     synchronisation.  When a call returns, `stream` is ordered after the
  *     result.  Pointers are borrowed until that work has run.
  *   - Every function returns a decdec_status (0 = OK, negative = error);
- *     nothing throws, aborts or prints.  On error nothing has been enqueued.
+ *     nothing throws, aborts or prints.  A call that fails validation
+ *     (EINVAL, EUNSUPPORTED, ENOTPINNED) has enqueued nothing.  A
+ *     call that fails with EHIP (a launch was refused) may have enqueued some
+ *     of its kernels already: y is then undefined, the stream stays usable
+ *     (in TWO_STREAMS mode the second stream has been joined back) and the
+ *     workspace cleans up after itself on its next call.
+ *   - Alignment: x, Wq, the codebook, residual rows and residual scales are
+ *     read with 128-bit loads and must be 16-byte aligned; fp16 arrays that are
+ *     read or written element-wise (scales, zero points, y, xsel) 2-byte and
+ *     index arrays 4-byte aligned.  Anything else is DECDEC_EINVAL.
  *   - A workspace serialises its users: calls that share one decdec_ws must
  *     be issued on one stream (or otherwise ordered); use one workspace per
  *     concurrent stream.
@@ -101,13 +110,24 @@ typedef struct decdec_ws decdec_ws; /* opaque workspace */
  * output buffers.  One workspace can be reused for every layer. */
 int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out);
 int decdec_ws_destroy(decdec_ws* ws);
-/* Size in bytes of the sc_indices + x[sc_indices] buffer for k channels. */
+/* Size in bytes of the sc_indices + x[sc_indices] buffer for k channels: the
+ * only extra GPU memory of the paper's kernel (Section 4.3: 1433 channels ->
+ * 8.6 KB). */
 size_t decdec_sc_buffer_bytes(int32_t k);
+/* Size in bytes of the fp32 partial rows a workspace for maxN output columns
+ * holds in addition: the base GEMV splits K over workgroups and the residual
+ * kernel splits the selected rows, each leaves up to 64 partial rows of maxN
+ * floats, and a fixed-order sum of those rows replaces the paper's atomic adds
+ * into o_b.  That is 512 maxN bytes (14.7 MB for the 28672 columns of gate + up
+ * of Llama-3-8B): extra GPU memory the paper's design does not need, the price
+ * of a result that does not depend on the order of floating-point atomics. */
+size_t decdec_partial_buffer_bytes(int32_t maxN);
 /* Device pointers to the selection of the most recent decdec_gemv call on
  * this workspace (valid once that call's work has run). */
 int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const void** xsel_f16_dev);
-/* Diagnostic, synchronous: waits for the workspace's side stream and copies
- * the first k entries of that selection to host arrays (either may be NULL). */
+/* Diagnostic, synchronous: waits for the whole device (the selection may have
+ * been written from any stream) and copies the first k entries of that
+ * selection to host arrays (either may be NULL). */
 int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, void* xsel_f16_host);
 
 /* Number of fetch workgroups per output-column block the residual kernel
@@ -146,6 +166,12 @@ int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on);
 /* Number of 128-channel groups each wavefront of the base GEMV walks through
  * (how finely K is split over the chip); 0 restores the built-in choice. */
 int decdec_ws_set_gemv_split(decdec_ws* ws, int32_t groups_per_wave);
+/* Wavefronts per workgroup (4, 8 or 16; 0 restores the built-in choice) of the
+ * base GEMV when it runs as a kernel of its own.  A workgroup adds the sums of
+ * its wavefronts; when waves x groups_per_wave covers all of K and there is no
+ * residual term (k == 0) the kernel writes y itself and nothing else is
+ * launched. */
+int decdec_ws_set_gemv_waves(decdec_ws* ws, int32_t waves_per_workgroup);
 
 /* Kernel timing for benchmarks.  capacity > 0 allocates that many sets of HIP
  * events (set-up call: allocates, synchronises) and makes every later
@@ -160,6 +186,22 @@ int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity);
  * (calls[4]); class 0: base GEMV, 1: selection, 2: residual fetch + residual
  * GEMV, 3: accumulate.  Starts over afterwards.  Either pointer may be NULL. */
 int decdec_ws_read_profile(decdec_ws* ws, double* ms, int32_t* calls);
+/* The same read-out (synchronous, starts over afterwards), but listing the
+ * duration in milliseconds of every timed launch of one kernel class in call
+ * order: at most `capacity` values go to ms_per_launch, *count_out receives how
+ * many.  Lets a benchmark attribute launches to the shapes it issued. */
+int decdec_ws_read_profile_launches(decdec_ws* ws, int32_t kernel_class, float* ms_per_launch, int32_t capacity,
+                                    int32_t* count_out);
+
+/* A workspace verifies every residual pointer once (one query of its memory
+ * type and of the extent of its allocation, the first time a hot-path call
+ * sees it) and remembers about 3000 of them; later calls only look it up, so
+ * a decode step of any depth costs no query and may be captured into a graph.
+ * Call this before freeing residual memory whose address may be reused for
+ * something else: p == NULL forgets every pointer. */
+int decdec_ws_forget_pointer(decdec_ws* ws, const void* p);
+/* Diagnostic: number of pointer queries this workspace has made so far. */
+int64_t decdec_ws_pointer_queries(const decdec_ws* ws);
 
 /* ------------------------------------------------- host helpers (offline) */
 
@@ -231,11 +273,14 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  * plain quantised GEMV.
  * The call only enqueues kernels (plus, in TWO_STREAMS mode, event records and
  * waits on the workspace's second stream), so it may be captured into a HIP
- * graph; the first call that sees a given R_pinned queries the pointer's
- * attributes, so call once (or decdec_check_pinned) before capturing.  Calls
+ * graph.  The first call that sees a given R_pinned queries the pointer's
+ * memory type and the extent of its allocation (two host-side runtime
+ * queries, no stream work, so this too is legal during capture); every later
+ * call finds it in the workspace's table (decdec_ws_forget_pointer).  Calls
  * that share a workspace must be ordered on one stream: they share its
  * partial-row and selection buffers.
- * Errors: DECDEC_EINVAL for null / out-of-range arguments, DECDEC_EUNSUPPORTED
+ * Errors: DECDEC_EINVAL for null / misaligned / out-of-range arguments and for
+ * a residual allocation shorter than K rows, DECDEC_EUNSUPPORTED
  * for a format combination that is not built, DECDEC_ENOTPINNED if R_pinned
  * is neither pinned host memory nor device memory, DECDEC_EHIP for a failed launch
  * (decdec_last_hip_error); nothing is enqueued when validation fails. */

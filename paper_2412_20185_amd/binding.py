@@ -23,9 +23,11 @@ R_FMT_OF_BITS = {16: R_FP16, 4: R_INT4_SYM_COL, 2: R_INT2_SYM_COL, 8: R_INT8_SYM
 
 EXPORTED_SYMBOLS = (
     "decdec_ws_create", "decdec_ws_destroy", "decdec_sc_buffer_bytes", "decdec_ws_last_selection",
-    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
+    "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_gemv_waves", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_pack_residual_int", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
+    "decdec_partial_buffer_bytes", "decdec_ws_read_profile_launches", "decdec_ws_forget_pointer",
+    "decdec_ws_pointer_queries",
     "decdec_quantize_uniform", "decdec_residual_f32", "decdec_quantize_residual", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned", "decdec_check_residual_pointer",
 )
 
@@ -70,6 +72,12 @@ def lib() -> C.CDLL:
     L.decdec_last_hip_error.restype = C.c_int
     L.decdec_sc_buffer_bytes.restype = sz
     L.decdec_sc_buffer_bytes.argtypes = [i32]
+    L.decdec_partial_buffer_bytes.restype = sz
+    L.decdec_partial_buffer_bytes.argtypes = [i32]
+    L.decdec_ws_read_profile_launches.argtypes = [vp, i32, C.POINTER(C.c_float), i32, C.POINTER(i32)]
+    L.decdec_ws_forget_pointer.argtypes = [vp, vp]
+    L.decdec_ws_pointer_queries.restype = C.c_int64
+    L.decdec_ws_pointer_queries.argtypes = [vp]
     L.decdec_check_pinned.argtypes = [vp]
     L.decdec_check_residual_pointer.argtypes = [vp]
     L.decdec_ws_create.argtypes = [i32, i32, i32, C.POINTER(vp)]
@@ -79,6 +87,7 @@ def lib() -> C.CDLL:
     L.decdec_ws_set_fetch_split.argtypes = [vp, i32]
     L.decdec_ws_set_profiling.argtypes = [vp, i32]
     L.decdec_ws_set_gemv_split.argtypes = [vp, i32]
+    L.decdec_ws_set_gemv_waves.argtypes = [vp, i32]
     L.decdec_ws_set_inkernel_accumulate.argtypes = [vp, i32]
     L.decdec_ws_set_separate_select.argtypes = [vp, i32]
     L.decdec_ws_set_mode.argtypes = [vp, i32]
@@ -132,6 +141,11 @@ def decdec_sc_buffer_bytes(k: int) -> int:
     return int(lib().decdec_sc_buffer_bytes(k))
 
 
+def decdec_partial_buffer_bytes(maxN: int) -> int:
+    return int(lib().decdec_partial_buffer_bytes(maxN))
+
+
+
 def decdec_check_pinned(t) -> int:
     return int(lib().decdec_check_pinned(_ptr(t)))
 
@@ -165,6 +179,9 @@ class Workspace:
     def set_gemv_split(self, groups_per_wave: int):
         _check(lib().decdec_ws_set_gemv_split(self.handle, groups_per_wave), "decdec_ws_set_gemv_split")
 
+    def set_gemv_waves(self, waves_per_workgroup: int):
+        _check(lib().decdec_ws_set_gemv_waves(self.handle, waves_per_workgroup), "decdec_ws_set_gemv_waves")
+
     def set_profiling(self, capacity: int):
         _check(lib().decdec_ws_set_profiling(self.handle, capacity), "decdec_ws_set_profiling")
 
@@ -175,6 +192,23 @@ class Workspace:
         n = (C.c_int32 * 4)()
         _check(lib().decdec_ws_read_profile(self.handle, ms, n), "decdec_ws_read_profile")
         return {name: (ms[i], n[i]) for i, name in enumerate(("gemv", "select", "fetch", "accumulate"))}
+
+    KERNEL_CLASSES = ("gemv", "select", "fetch", "accumulate")
+
+    def read_profile_launches(self, kernel_class: str, capacity: int = 1 << 16):
+        """Synchronous: the duration (ms) of every timed launch of one kernel class since the last read, in
+        call order (this read starts the record over, like read_profile)."""
+        buf = (C.c_float * capacity)()
+        n = C.c_int32()
+        _check(lib().decdec_ws_read_profile_launches(self.handle, self.KERNEL_CLASSES.index(kernel_class), buf,
+                                                     capacity, C.byref(n)), "decdec_ws_read_profile_launches")
+        return [buf[i] for i in range(n.value)]
+
+    def forget_pointer(self, t=None):
+        _check(lib().decdec_ws_forget_pointer(self.handle, _ptr(t)), "decdec_ws_forget_pointer")
+
+    def pointer_queries(self) -> int:
+        return int(lib().decdec_ws_pointer_queries(self.handle))
 
     def last_selection_ptrs(self):
         a, b = C.c_void_p(), C.c_void_p()

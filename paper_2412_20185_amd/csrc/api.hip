@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "../../include/decdec.h"
@@ -48,34 +49,104 @@ int check_desc(const decdec_desc* d) {
     return DECDEC_OK;
 }
 
-constexpr int kPinnedCache = 16;
 constexpr int kProfClasses = 4;              // base GEMV, selection, fetch, accumulate
 constexpr int kProfEvents = 2 * kProfClasses;  // a (start, stop) pair each
 
-}  // namespace
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-struct decdec_ws {
+// Residual pointers that have been verified (one attribute query per pointer, ever): an open-addressing
+// table over storage the owner supplies, so that looking a pointer up or adding one never allocates.
+struct PtrEntry {
+    const void* p;      // null: free slot
+    size_t avail;       // bytes of the allocation from p to its end; SIZE_MAX when the runtime does not say
+    uint8_t in_device;  // 1: device memory, 0: pinned host memory
+};
+
+struct PointerTable {
+    PtrEntry* e;
+    int cap;  // a power of two
+    int used;
+    long long queries;  // attribute queries made so far
+
+    size_t slot(const void* p) const {
+        uint64_t v = reinterpret_cast<uintptr_t>(p);
+        v ^= v >> 17;
+        v *= 0x9E3779B97F4A7C15ull;
+        return (size_t)(v >> 24) & (size_t)(cap - 1);
+    }
+    const PtrEntry* find(const void* p) const {
+        for (size_t i = slot(p), n = 0; n < (size_t)cap; i = (i + 1) & (size_t)(cap - 1), ++n) {
+            if (e[i].p == p) return &e[i];
+            if (e[i].p == nullptr) return nullptr;
+        }
+        return nullptr;
+    }
+    // False when the table is three quarters full: the pointer is then verified again on its next use.
+    bool insert(const PtrEntry& x) {
+        if (used >= cap - cap / 4) return false;
+        size_t i = slot(x.p);
+        while (e[i].p != nullptr && e[i].p != x.p) i = (i + 1) & (size_t)(cap - 1);
+        if (e[i].p == nullptr) ++used;
+        e[i] = x;
+        return true;
+    }
+    void clear() {
+        std::memset(e, 0, sizeof(PtrEntry) * (size_t)cap);
+        used = 0;
+    }
+    // Linear probing without tombstones: the entries behind the hole move up.
+    void erase(const void* p) {
+        size_t i = slot(p);
+        for (size_t n = 0; n < (size_t)cap && e[i].p != p; ++n) {
+            if (e[i].p == nullptr) return;
+            i = (i + 1) & (size_t)(cap - 1);
+        }
+        if (e[i].p != p) return;
+        e[i].p = nullptr;
+        --used;
+        for (size_t j = (i + 1) & (size_t)(cap - 1); e[j].p != nullptr; j = (j + 1) & (size_t)(cap - 1)) {
+            const PtrEntry x = e[j];
+            e[j].p = nullptr;
+            --used;
+            insert(x);
+        }
+    }
+};
+
+constexpr int kWsPointerSlots = 4096;      // a workspace remembers about 3000 residual pointers (a 32-layer model has 224)
+constexpr int kStaticPointerSlots = 1024;  // the allocation-free entry point: about 750 per GPU
+
+// What one compensated GEMV needs besides its operands: scratch buffers, options and the table of verified
+// residual pointers.  A workspace owns one (buffers from hipMalloc); the allocation-free entry point keeps one
+// per GPU whose buffers lie in a static device array.
+struct Core {
     int32_t maxK, maxN, maxk;
     int32_t fetch_split;
     int32_t gemv_gpw;
-    hipStream_t side;
-    hipEvent_t ev_fork, ev_join;
-    int32_t* idx;    // [maxk]
-    void* xsel;      // fp16 [maxk]
-    float* gpart;    // [kMaxGemvSlices][maxN]
-    float* cpart;    // [kMaxFetchSlices][maxN]
-    unsigned* counters;  // [maxN/64] per-tile arrival counters, zero between calls
+    int32_t gemv_wpb;             // wavefronts per base-GEMV workgroup when it runs as a kernel of its own; 0: built in
     int32_t mode;                 // decdec_mode
     int32_t separate_select;      // 1: selection always runs as a kernel of its own
     int32_t inkernel_accumulate;  // 1: the last producer of a tile adds the partial rows (no accumulate kernel)
     int32_t counters_dirty;       // a call failed half-way: clear the counters before the next one
-    const void* pinned_ok[kPinnedCache];  // residual base pointers already verified
-    uint8_t pinned_dev[kPinnedCache];     // 1: that pointer is device memory
-    int pinned_n, pinned_next;
+    int32_t* idx;        // [maxk]
+    void* xsel;          // fp16 [maxk]
+    float* gpart;        // [kMaxGemvSlices][maxN]
+    float* cpart;        // [kMaxFetchSlices][maxN]
+    unsigned* counters;  // [maxN/64 + 1] per-tile arrival counters, zero between calls
+    hipStream_t side;    // null: no second stream (TWO_STREAMS mode unavailable)
+    hipEvent_t ev_fork, ev_join;
+    PointerTable ptrs;
     // optional kernel timing: per call one (start, stop) event pair per kernel class
-    hipEvent_t* prof_ev;   // [prof_cap][kProfEvents]: gemv, select, fetch, accumulate
-    uint8_t* prof_mask;    // [prof_cap] bit c: class c was launched and timed
+    hipEvent_t* prof_ev;  // [prof_cap][kProfEvents]: gemv, select, fetch, accumulate
+    uint8_t* prof_mask;   // [prof_cap] bit c: class c was launched and timed
     int32_t prof_cap, prof_used;
+};
+
+}  // namespace
+
+struct decdec_ws {
+    Core core;
+    PtrEntry slots[kWsPointerSlots];
 };
 
 extern "C" {
@@ -95,6 +166,10 @@ const char* decdec_strerror(int status) {
 int decdec_last_hip_error(void) { return g_last_hip_error; }
 
 size_t decdec_sc_buffer_bytes(int32_t k) { return k > 0 ? (size_t)k * (4 + 2) : 0; }
+
+size_t decdec_partial_buffer_bytes(int32_t maxN) {
+    return maxN > 0 ? (size_t)(kMaxGemvSlices + kMaxFetchSlices) * (size_t)maxN * 4 : 0;
+}
 
 // hipMemoryTypeHost / hipMemoryTypeDevice, or -1 for memory the GPU cannot read.
 static int residual_memory_type(const void* p) {
@@ -125,19 +200,22 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
     decdec_ws* ws = new (std::nothrow) decdec_ws();
     if (ws == nullptr) return DECDEC_ENOMEM;
     std::memset(ws, 0, sizeof(*ws));
-    ws->maxK = maxK;
-    ws->maxN = maxN;
-    ws->maxk = maxk;
+    Core& c = ws->core;
+    c.maxK = maxK;
+    c.maxN = maxN;
+    c.maxk = maxk;
+    c.ptrs.e = ws->slots;
+    c.ptrs.cap = kWsPointerSlots;
     const size_t kk = maxk > 0 ? (size_t)maxk : 1;
-    hipError_t e = hipStreamCreateWithFlags(&ws->side, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&ws->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&ws->ev_join, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->idx), kk * 4);
-    if (e == hipSuccess) e = hipMalloc(&ws->xsel, kk * 2);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->gpart), (size_t)kMaxGemvSlices * maxN * 4);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->cpart), (size_t)kMaxFetchSlices * maxN * 4);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ws->counters), ((size_t)maxN / 64 + 1) * 4);
-    if (e == hipSuccess) e = hipMemset(ws->counters, 0, ((size_t)maxN / 64 + 1) * 4);
+    hipError_t e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c.ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.idx), kk * 4);
+    if (e == hipSuccess) e = hipMalloc(&c.xsel, kk * 2);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.gpart), (size_t)kMaxGemvSlices * maxN * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.cpart), (size_t)kMaxFetchSlices * maxN * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.counters), ((size_t)maxN / 64 + 1) * 4);
+    if (e == hipSuccess) e = hipMemset(c.counters, 0, ((size_t)maxN / 64 + 1) * 4);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         const int rc = e == hipErrorOutOfMemory ? DECDEC_ENOMEM : hip_fail(e);
@@ -149,133 +227,174 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
     return DECDEC_OK;
 }
 
-static void free_profiling(decdec_ws* ws) {
-    if (ws->prof_ev) {
-        for (int i = 0; i < ws->prof_cap * kProfEvents; ++i)
-            if (ws->prof_ev[i]) (void)hipEventDestroy(ws->prof_ev[i]);
-        delete[] ws->prof_ev;
-        delete[] ws->prof_mask;
+static void free_profiling(Core& c) {
+    if (c.prof_ev) {
+        for (int i = 0; i < c.prof_cap * kProfEvents; ++i)
+            if (c.prof_ev[i]) (void)hipEventDestroy(c.prof_ev[i]);
+        delete[] c.prof_ev;
+        delete[] c.prof_mask;
     }
-    ws->prof_ev = nullptr;
-    ws->prof_mask = nullptr;
-    ws->prof_cap = ws->prof_used = 0;
+    c.prof_ev = nullptr;
+    c.prof_mask = nullptr;
+    c.prof_cap = c.prof_used = 0;
 }
 
 int decdec_ws_set_profiling(decdec_ws* ws, int32_t capacity) {
     if (ws == nullptr || capacity < 0 || capacity > (1 << 20)) return DECDEC_EINVAL;
+    Core& c = ws->core;
     DD_HIP(hipDeviceSynchronize());
-    free_profiling(ws);
+    free_profiling(c);
     if (capacity == 0) return DECDEC_OK;
-    ws->prof_ev = new (std::nothrow) hipEvent_t[(size_t)capacity * kProfEvents]();
-    ws->prof_mask = new (std::nothrow) uint8_t[capacity]();
-    if (ws->prof_ev == nullptr || ws->prof_mask == nullptr) {
-        delete[] ws->prof_ev;
-        delete[] ws->prof_mask;
-        ws->prof_ev = nullptr;
-        ws->prof_mask = nullptr;
+    c.prof_ev = new (std::nothrow) hipEvent_t[(size_t)capacity * kProfEvents]();
+    c.prof_mask = new (std::nothrow) uint8_t[capacity]();
+    if (c.prof_ev == nullptr || c.prof_mask == nullptr) {
+        delete[] c.prof_ev;
+        delete[] c.prof_mask;
+        c.prof_ev = nullptr;
+        c.prof_mask = nullptr;
         return DECDEC_ENOMEM;
     }
-    ws->prof_cap = capacity;
+    c.prof_cap = capacity;
     for (int i = 0; i < capacity * kProfEvents; ++i) {
-        const hipError_t e = hipEventCreate(&ws->prof_ev[i]);
+        const hipError_t e = hipEventCreate(&c.prof_ev[i]);
         if (e != hipSuccess) {
-            free_profiling(ws);
+            free_profiling(c);
             return hip_fail(e);
         }
     }
     return DECDEC_OK;
 }
 
-int decdec_ws_read_profile(decdec_ws* ws, double* ms_out, int32_t* calls_out) {
-    if (ws == nullptr) return DECDEC_EINVAL;
+// Per kernel class: summed durations (ms) and launch counts; with per_launch != null also the duration of
+// every timed launch of class `cls` in call order (at most per_launch_cap of them, *per_launch_n receives the count).
+static int read_profile(Core& c, double* ms_out, int32_t* calls_out, int cls, float* per_launch, int per_launch_cap,
+                        int32_t* per_launch_n) {
     double t[kProfClasses] = {0, 0, 0, 0};
     int32_t n[kProfClasses] = {0, 0, 0, 0};
-    if (ws->prof_ev) {
+    int32_t listed = 0;
+    if (c.prof_ev) {
         DD_HIP(hipDeviceSynchronize());
-        for (int i = 0; i < ws->prof_used; ++i) {
-            hipEvent_t* ev = ws->prof_ev + (size_t)i * kProfEvents;
-            for (int c = 0; c < kProfClasses; ++c) {
-                if (ws->prof_mask[i] & (1 << c)) {
+        for (int i = 0; i < c.prof_used; ++i) {
+            hipEvent_t* ev = c.prof_ev + (size_t)i * kProfEvents;
+            for (int k = 0; k < kProfClasses; ++k) {
+                if (c.prof_mask[i] & (1 << k)) {
                     float ms = 0.f;
-                    DD_HIP(hipEventElapsedTime(&ms, ev[2 * c], ev[2 * c + 1]));
-                    t[c] += ms;
-                    ++n[c];
+                    DD_HIP(hipEventElapsedTime(&ms, ev[2 * k], ev[2 * k + 1]));
+                    t[k] += ms;
+                    ++n[k];
+                    if (k == cls && per_launch != nullptr && listed < per_launch_cap) per_launch[listed++] = ms;
                 }
             }
-            ws->prof_mask[i] = 0;
+            c.prof_mask[i] = 0;
         }
-        ws->prof_used = 0;
+        c.prof_used = 0;
     }
-    for (int c = 0; c < kProfClasses; ++c) {
-        if (ms_out) ms_out[c] = t[c];
-        if (calls_out) calls_out[c] = n[c];
+    for (int k = 0; k < kProfClasses; ++k) {
+        if (ms_out) ms_out[k] = t[k];
+        if (calls_out) calls_out[k] = n[k];
     }
+    if (per_launch_n) *per_launch_n = listed;
     return DECDEC_OK;
+}
+
+int decdec_ws_read_profile(decdec_ws* ws, double* ms_out, int32_t* calls_out) {
+    if (ws == nullptr) return DECDEC_EINVAL;
+    return read_profile(ws->core, ms_out, calls_out, -1, nullptr, 0, nullptr);
+}
+
+int decdec_ws_read_profile_launches(decdec_ws* ws, int32_t kernel_class, float* ms_per_launch, int32_t capacity,
+                                    int32_t* count_out) {
+    if (ws == nullptr || kernel_class < 0 || kernel_class >= kProfClasses || ms_per_launch == nullptr ||
+        capacity < 0 || count_out == nullptr)
+        return DECDEC_EINVAL;
+    return read_profile(ws->core, nullptr, nullptr, kernel_class, ms_per_launch, capacity, count_out);
 }
 
 int decdec_ws_destroy(decdec_ws* ws) {
     if (ws == nullptr) return DECDEC_OK;
-    free_profiling(ws);
-    if (ws->side) {
-        (void)hipStreamSynchronize(ws->side);
-        (void)hipStreamDestroy(ws->side);
+    Core& c = ws->core;
+    free_profiling(c);
+    if (c.side) {
+        (void)hipStreamSynchronize(c.side);
+        (void)hipStreamDestroy(c.side);
     }
-    if (ws->ev_fork) (void)hipEventDestroy(ws->ev_fork);
-    if (ws->ev_join) (void)hipEventDestroy(ws->ev_join);
-    if (ws->idx) (void)hipFree(ws->idx);
-    if (ws->xsel) (void)hipFree(ws->xsel);
-    if (ws->gpart) (void)hipFree(ws->gpart);
-    if (ws->cpart) (void)hipFree(ws->cpart);
-    if (ws->counters) (void)hipFree(ws->counters);
+    if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
+    if (c.ev_join) (void)hipEventDestroy(c.ev_join);
+    if (c.idx) (void)hipFree(c.idx);
+    if (c.xsel) (void)hipFree(c.xsel);
+    if (c.gpart) (void)hipFree(c.gpart);
+    if (c.cpart) (void)hipFree(c.cpart);
+    if (c.counters) (void)hipFree(c.counters);
     delete ws;
     return DECDEC_OK;
 }
 
 int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const void** xsel_f16_dev) {
     if (ws == nullptr) return DECDEC_EINVAL;
-    if (idx_dev) *idx_dev = ws->idx;
-    if (xsel_f16_dev) *xsel_f16_dev = ws->xsel;
+    if (idx_dev) *idx_dev = ws->core.idx;
+    if (xsel_f16_dev) *xsel_f16_dev = ws->core.xsel;
     return DECDEC_OK;
 }
 
 int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on) {
     if (ws == nullptr || (on != 0 && on != 1)) return DECDEC_EINVAL;
-    ws->inkernel_accumulate = on;
+    ws->core.inkernel_accumulate = on;
     return DECDEC_OK;
 }
 
 int decdec_ws_set_mode(decdec_ws* ws, int32_t mode) {
     if (ws == nullptr || mode < DECDEC_MODE_FUSED || mode > DECDEC_MODE_TWO_STREAMS) return DECDEC_EINVAL;
-    ws->mode = mode;
+    ws->core.mode = mode;
     return DECDEC_OK;
 }
 
 int decdec_ws_set_separate_select(decdec_ws* ws, int32_t on) {
     if (ws == nullptr || (on != 0 && on != 1)) return DECDEC_EINVAL;
-    ws->separate_select = on;
+    ws->core.separate_select = on;
     return DECDEC_OK;
 }
 
 int decdec_ws_set_gemv_split(decdec_ws* ws, int32_t groups_per_wave) {
     if (ws == nullptr || groups_per_wave < 0 || groups_per_wave > 1024) return DECDEC_EINVAL;
-    ws->gemv_gpw = groups_per_wave;
+    ws->core.gemv_gpw = groups_per_wave;
+    return DECDEC_OK;
+}
+
+int decdec_ws_set_gemv_waves(decdec_ws* ws, int32_t waves_per_workgroup) {
+    if (ws == nullptr || (waves_per_workgroup != 0 && waves_per_workgroup != 4 && waves_per_workgroup != 8 &&
+                          waves_per_workgroup != 16))
+        return DECDEC_EINVAL;
+    ws->core.gemv_wpb = waves_per_workgroup;
     return DECDEC_OK;
 }
 
 int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, void* xsel_f16_host) {
-    if (ws == nullptr || k < 0 || k > ws->maxk) return DECDEC_EINVAL;
-    DD_HIP(hipStreamSynchronize(ws->side));
+    if (ws == nullptr || k < 0 || k > ws->core.maxk) return DECDEC_EINVAL;
+    // The selection may have been written by a kernel on any stream of the caller's: wait for the device.
+    DD_HIP(hipDeviceSynchronize());
     if (k == 0) return DECDEC_OK;
-    if (idx_host) DD_HIP(hipMemcpy(idx_host, ws->idx, (size_t)k * 4, hipMemcpyDeviceToHost));
-    if (xsel_f16_host) DD_HIP(hipMemcpy(xsel_f16_host, ws->xsel, (size_t)k * 2, hipMemcpyDeviceToHost));
+    if (idx_host) DD_HIP(hipMemcpy(idx_host, ws->core.idx, (size_t)k * 4, hipMemcpyDeviceToHost));
+    if (xsel_f16_host) DD_HIP(hipMemcpy(xsel_f16_host, ws->core.xsel, (size_t)k * 2, hipMemcpyDeviceToHost));
     return DECDEC_OK;
 }
 
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split) {
     if (ws == nullptr || row_split < 0 || row_split > kMaxFetchSlices) return DECDEC_EINVAL;
-    ws->fetch_split = row_split;
+    ws->core.fetch_split = row_split;
     return DECDEC_OK;
 }
+
+int decdec_ws_forget_pointer(decdec_ws* ws, const void* p) {
+    if (ws == nullptr) return DECDEC_EINVAL;
+    if (p == nullptr) {
+        ws->core.ptrs.clear();
+    } else {
+        ws->core.ptrs.erase(p);
+    }
+    return DECDEC_OK;
+}
+
+int64_t decdec_ws_pointer_queries(const decdec_ws* ws) { return ws == nullptr ? -1 : (int64_t)ws->core.ptrs.queries; }
 
 // ------------------------------------------------------------ host helpers
 
@@ -372,8 +491,9 @@ int decdec_pack_residual_int4(int32_t K, int32_t N, const int8_t* codes_KN, uint
 int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k, int32_t* idx_out_dev, void* xsel_f16_dev,
                        void* stream) {
     if (x_f16_dev == nullptr || K < 8 || K % 8 != 0 || K > kSelectMaxK || k < 0 || k > K) return DECDEC_EINVAL;
+    if (!aligned(x_f16_dev, 16)) return DECDEC_EINVAL;
     if (k == 0) return DECDEC_OK;
-    if (idx_out_dev == nullptr) return DECDEC_EINVAL;
+    if (idx_out_dev == nullptr || !aligned(idx_out_dev, 4) || !aligned(xsel_f16_dev, 2)) return DECDEC_EINVAL;
     DD_HIP(launch_select_topk(x_f16_dev, K, k, idx_out_dev, xsel_f16_dev, static_cast<hipStream_t>(stream)));
     return DECDEC_OK;
 }
@@ -381,37 +501,55 @@ int decdec_select_topk(const void* x_f16_dev, int32_t K, int32_t k, int32_t* idx
 int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, float b0, float b15,
                          int32_t* idx_out_dev, void* xsel_f16_dev, void* stream) {
     if (x_f16_dev == nullptr || K < 1024 || K % 1024 != 0 || k_chunk < 0 || k_chunk > 1024) return DECDEC_EINVAL;
+    if (!aligned(x_f16_dev, 16)) return DECDEC_EINVAL;
     if (!(b0 >= b15) || !(b15 >= 0.f)) return DECDEC_EINVAL;  // also rejects NaN
     if (k_chunk == 0) return DECDEC_OK;
-    if (idx_out_dev == nullptr) return DECDEC_EINVAL;
+    if (idx_out_dev == nullptr || !aligned(idx_out_dev, 4) || !aligned(xsel_f16_dev, 2)) return DECDEC_EINVAL;
     DD_HIP(launch_select_bucket(x_f16_dev, K, k_chunk, b0, b15, idx_out_dev, xsel_f16_dev,
                                 static_cast<hipStream_t>(stream)));
     return DECDEC_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Looks the residual pointer up; a pointer seen for the first time is verified with one attribute query and
+// one address-range query and then remembered.  need: bytes the kernels may read from R on (K rows).
 // *in_device: the residuals live in device memory (not over the host link).
-static int check_pinned_cached(decdec_ws* ws, const void* R_pinned, bool* in_device) {
-    for (int i = 0; i < ws->pinned_n; ++i) {
-        if (ws->pinned_ok[i] == R_pinned) {
-            *in_device = ws->pinned_dev[i] != 0;
-            return DECDEC_OK;
+int check_residual_cached(PointerTable& tab, const void* R, size_t need, bool* in_device) {
+    const PtrEntry* hit = tab.find(R);
+    PtrEntry fresh;
+    if (hit == nullptr) {
+        ++tab.queries;
+        const int type = residual_memory_type(R);
+        if (type < 0) return DECDEC_ENOTPINNED;
+        fresh.p = R;
+        fresh.in_device = type == (int)hipMemoryTypeDevice ? 1 : 0;
+        fresh.avail = SIZE_MAX;
+        void* base = nullptr;
+        size_t size = 0;
+        if (hipMemGetAddressRange(reinterpret_cast<hipDeviceptr_t*>(&base), &size, const_cast<void*>(R)) == hipSuccess &&
+            base != nullptr && size > 0) {
+            const uintptr_t end = reinterpret_cast<uintptr_t>(base) + size, at = reinterpret_cast<uintptr_t>(R);
+            if (at >= reinterpret_cast<uintptr_t>(base) && at < end) fresh.avail = (size_t)(end - at);
+        } else {
+            (void)hipGetLastError();  // not every kind of pinned memory reports its range
         }
+        (void)tab.insert(fresh);
+        hit = &fresh;
     }
-    const int type = residual_memory_type(R_pinned);
-    if (type < 0) return DECDEC_ENOTPINNED;
-    *in_device = type == (int)hipMemoryTypeDevice;
-    ws->pinned_ok[ws->pinned_next] = R_pinned;
-    ws->pinned_dev[ws->pinned_next] = *in_device ? 1 : 0;
-    ws->pinned_next = (ws->pinned_next + 1) % kPinnedCache;
-    if (ws->pinned_n < kPinnedCache) ++ws->pinned_n;
+    if (need > hit->avail) return DECDEC_EINVAL;  // the allocation is shorter than K rows
+    *in_device = hit->in_device != 0;
     return DECDEC_OK;
 }
 
 // count linears that share x (and therefore K, the selection, and one launch
 // of each kernel).  idx_in/xsel_in: caller-supplied selection or null.
-static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t k, const int32_t* idx_in,
-                       const void* xsel_in, bool have_idx, decdec_ws* ws, void* stream_v) {
-    if (lin == nullptr || count < 1 || count > kMaxMulti || ws == nullptr || x == nullptr) return DECDEC_EINVAL;
+int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t k, const int32_t* idx_in,
+                const void* xsel_in, bool have_idx, Core* core, void* stream_v) {
+    if (lin == nullptr || count < 1 || count > kMaxMulti || core == nullptr || x == nullptr) return DECDEC_EINVAL;
+    Core& c = *core;
     MultiShape sh{};
     GemvOperands gop{};
     FetchOperands fop{};
@@ -427,6 +565,9 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
             return DECDEC_EUNSUPPORTED;
         if (L.Wq_dev == nullptr || L.zeros_or_lut_f16_dev == nullptr || L.y_f16_dev == nullptr) return DECDEC_EINVAL;
         if (L.desc->wfmt == DECDEC_W_UNIFORM_G128 && L.scales_f16_dev == nullptr) return DECDEC_EINVAL;
+        // what the kernels' vector and scalar loads assume
+        if (!aligned(L.Wq_dev, 16) || !aligned(L.y_f16_dev, 2) || !aligned(L.scales_f16_dev, 2)) return DECDEC_EINVAL;
+        if (!aligned(L.zeros_or_lut_f16_dev, L.desc->wfmt == DECDEC_W_LUT_COL8 ? 16 : 2)) return DECDEC_EINVAL;
         sh.N[m] = L.desc->N;
         sh.col0[m + 1] = sh.col0[m] + L.desc->N;
         gop.Wq[m] = L.Wq_dev;
@@ -437,15 +578,24 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
         ys[m] = L.y_f16_dev;
     }
     sh.K = d0->K;
-    if (sh.K > ws->maxK || sh.col0[count] > ws->maxN || k < 0 || k > sh.K || k > ws->maxk) return DECDEC_EINVAL;
+    if (!aligned(x, 16)) return DECDEC_EINVAL;
+    if (sh.K > c.maxK || sh.col0[count] > c.maxN || k < 0 || k > sh.K || k > c.maxk) return DECDEC_EINVAL;
+    if (c.mode == DECDEC_MODE_TWO_STREAMS && c.side == nullptr) return DECDEC_EUNSUPPORTED;
     bool residuals_in_hbm = k > 0;  // all of them: the fetch is then bound by HBM latency, not by the host link
     if (k > 0) {
-        if (have_idx && (idx_in == nullptr || xsel_in == nullptr)) return DECDEC_EINVAL;
+        if (have_idx && (idx_in == nullptr || xsel_in == nullptr || !aligned(idx_in, 4) || !aligned(xsel_in, 2)))
+            return DECDEC_EINVAL;
+        const int rbits = d0->rfmt == DECDEC_R_FP16 ? 16 : d0->rfmt == DECDEC_R_INT4_SYM_COL ? 4
+                        : d0->rfmt == DECDEC_R_INT2_SYM_COL ? 2 : 8;
         for (int m = 0; m < count; ++m) {
-            if (lin[m].R_pinned == nullptr) return DECDEC_EINVAL;
-            if (d0->rfmt != DECDEC_R_FP16 && lin[m].R_scales_f16_dev == nullptr) return DECDEC_EINVAL;
+            if (lin[m].R_pinned == nullptr || !aligned(lin[m].R_pinned, 16)) return DECDEC_EINVAL;
+            if (d0->rfmt != DECDEC_R_FP16 &&
+                (lin[m].R_scales_f16_dev == nullptr || !aligned(lin[m].R_scales_f16_dev, 16)))
+                return DECDEC_EINVAL;
+            if ((size_t)sh.N[m] * rbits % 128 != 0) return DECDEC_EINVAL;  // a row is a whole number of 16-byte pieces
             bool in_device = false;
-            const int prc = check_pinned_cached(ws, lin[m].R_pinned, &in_device);
+            const size_t need = (size_t)sh.K * ((size_t)sh.N[m] * rbits / 8);
+            const int prc = check_residual_cached(c.ptrs, lin[m].R_pinned, need, &in_device);
             if (prc != DECDEC_OK) return prc;
             residuals_in_hbm = residuals_in_hbm && in_device;
         }
@@ -455,14 +605,14 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     KernelTimer timers[kProfClasses];
     const KernelTimer* tm[kProfClasses] = {nullptr, nullptr, nullptr, nullptr};
     uint8_t* pmask = nullptr;
-    if (ws->prof_ev != nullptr && ws->prof_used < ws->prof_cap) {
-        hipEvent_t* ev = ws->prof_ev + (size_t)ws->prof_used * kProfEvents;
-        for (int c = 0; c < kProfClasses; ++c) {
-            timers[c] = KernelTimer{ev[2 * c], ev[2 * c + 1]};
-            tm[c] = &timers[c];
+    if (c.prof_ev != nullptr && c.prof_used < c.prof_cap) {
+        hipEvent_t* ev = c.prof_ev + (size_t)c.prof_used * kProfEvents;
+        for (int i = 0; i < kProfClasses; ++i) {
+            timers[i] = KernelTimer{ev[2 * i], ev[2 * i + 1]};
+            tm[i] = &timers[i];
         }
-        pmask = ws->prof_mask + ws->prof_used;
-        ++ws->prof_used;
+        pmask = c.prof_mask + c.prof_used;
+        ++c.prof_used;
     }
 
     // Split of the work, known up front because each kernel must know how many
@@ -470,12 +620,12 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
     long tiles = 0;
     for (int m = 0; m < count; ++m) tiles += sh.N[m] / kTileCols;
     // The one-grid kernel is built for fp16 and 4-bit residuals; the other formats take the separate kernels.
-    const bool fused = k > 0 && ws->mode == DECDEC_MODE_FUSED &&
+    const bool fused = k > 0 && c.mode == DECDEC_MODE_FUSED &&
                        (d0->rfmt == DECDEC_R_FP16 || d0->rfmt == DECDEC_R_INT4_SYM_COL);
     int gpw = 1;
-    const int gslices =
-        gemv_slices(tiles, sh.K / kGroup, ws->gemv_gpw, fused ? kWavesPerBlock : kGemvAloneWaves, &gpw);
-    const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, ws->fetch_split, residuals_in_hbm) : 0;
+    const int wpb = fused ? kWavesPerBlock : c.gemv_wpb > 0 ? c.gemv_wpb : kGemvAloneWaves;
+    const int gslices = gemv_slices(tiles, sh.K / kGroup, c.gemv_gpw, wpb, &gpw);
+    const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, c.fetch_split, residuals_in_hbm) : 0;
 
     FinalizeArgs fa{};
     int t0 = 0;
@@ -485,68 +635,82 @@ static int gemv_common(int32_t count, const decdec_linear* lin, const void* x, i
         fa.tile0[m] = t0;
         t0 += sh.N[m] / kTileCols;
     }
-    fa.gpart = ws->gpart;
-    fa.cpart = ws->cpart;
+    fa.gpart = c.gpart;
+    fa.cpart = c.cpart;
     fa.gslices = gslices;
     fa.cslices = cslices;
     fa.Ntot = sh.col0[count];
-    fa.counters = ws->inkernel_accumulate ? ws->counters : nullptr;
+    fa.counters = c.inkernel_accumulate ? c.counters : nullptr;
+    // One slice and no residual term: the base GEMV rounds and writes y itself, nothing is left to add.
+    fa.direct = k == 0 && gslices == 1 ? 1 : 0;
 
-    if (ws->counters_dirty) {
-        DD_HIP(launch_clear_u32(ws->counters, ws->maxN / 64 + 1, stream));
-        ws->counters_dirty = 0;
+    if (c.counters_dirty) {
+        DD_HIP(launch_clear_u32(c.counters, c.maxN / 64 + 1, stream));
+        c.counters_dirty = 0;
     }
+    bool forked = false;  // TWO_STREAMS: the side stream has been made to wait for `stream` and not yet joined back
     const int rc_enq = [&]() -> int {
         if (k == 0) {
-            DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, gslices, gpw, fa, stream, tm[0]));
+            DD_HIP(launch_gemv(kind, sh, gop, x, c.gpart, gslices, gpw, wpb, fa, stream, tm[0]));
             if (pmask) *pmask |= 1;
         } else {
             // The kernels that follow read idx / xsel only; the const is dropped for the shared signatures.
             int32_t* idx = const_cast<int32_t*>(idx_in);
             void* xsel = const_cast<void*>(xsel_in);
             int select_chunks = 0;
-            const bool two_streams = ws->mode == DECDEC_MODE_TWO_STREAMS;
-            hipStream_t comp = two_streams ? ws->side : stream;  // where steps 1-3 run
+            const bool two_streams = c.mode == DECDEC_MODE_TWO_STREAMS;
+            hipStream_t comp = two_streams ? c.side : stream;  // where steps 1-3 run
             if (two_streams) {
                 // Section 4.1 as printed: compensation on another stream than the base GEMV.
-                DD_HIP(hipEventRecord(ws->ev_fork, stream));
-                DD_HIP(hipStreamWaitEvent(ws->side, ws->ev_fork, 0));
+                DD_HIP(hipEventRecord(c.ev_fork, stream));
+                DD_HIP(hipStreamWaitEvent(c.side, c.ev_fork, 0));
+                forked = true;
             }
             if (!have_idx) {
-                idx = ws->idx;
-                xsel = ws->xsel;
-                select_chunks = ws->separate_select ? 0 : fetch_select_chunks(sh.K, k);
+                idx = c.idx;
+                xsel = c.xsel;
+                select_chunks = c.separate_select ? 0 : fetch_select_chunks(sh.K, k);
                 if (select_chunks == 0) {
-                    DD_HIP(launch_select_topk(x, sh.K, k, ws->idx, ws->xsel, comp, tm[1]));
+                    DD_HIP(launch_select_topk(x, sh.K, k, c.idx, c.xsel, comp, tm[1]));
                     if (pmask) *pmask |= 2;
                 }
             }
             if (fused) {
-                DD_HIP(launch_compensated_gemv(kind, d0->rfmt, sh, gop, fop, x, select_chunks, idx, xsel, k, ws->gpart,
-                                               gslices, gpw, ws->cpart, cslices, fa, stream, tm[2]));
+                DD_HIP(launch_compensated_gemv(kind, d0->rfmt, sh, gop, fop, x, select_chunks, idx, xsel, k, c.gpart,
+                                               gslices, gpw, c.cpart, cslices, fa, stream, tm[2]));
                 if (pmask) *pmask |= 4;
             } else {
-                DD_HIP(launch_fetch(d0->rfmt, sh, fop, x, select_chunks, idx, xsel, k, ws->cpart, cslices, fa, comp,
+                DD_HIP(launch_fetch(d0->rfmt, sh, fop, x, select_chunks, idx, xsel, k, c.cpart, cslices, fa, comp,
                                     tm[2]));
                 if (pmask) *pmask |= 4;
-                if (two_streams) DD_HIP(hipEventRecord(ws->ev_join, ws->side));
-                DD_HIP(launch_gemv(kind, sh, gop, x, ws->gpart, gslices, gpw, fa, stream, tm[0]));
+                if (two_streams) DD_HIP(hipEventRecord(c.ev_join, c.side));
+                DD_HIP(launch_gemv(kind, sh, gop, x, c.gpart, gslices, gpw, wpb, fa, stream, tm[0]));
                 if (pmask) *pmask |= 1;
-                if (two_streams) DD_HIP(hipStreamWaitEvent(stream, ws->ev_join, 0));
+                if (two_streams) {
+                    DD_HIP(hipStreamWaitEvent(stream, c.ev_join, 0));
+                    forked = false;
+                }
             }
         }
-        if (!ws->inkernel_accumulate) {
-            DD_HIP(launch_accumulate(sh, ys, ws->gpart, gslices, ws->cpart, cslices, stream, tm[3]));
+        if (!c.inkernel_accumulate && !fa.direct) {
+            DD_HIP(launch_accumulate(sh, ys, c.gpart, gslices, c.cpart, cslices, stream, tm[3]));
             if (pmask) *pmask |= 8;
         }
         return DECDEC_OK;
     }();
-    if (rc_enq != DECDEC_OK) ws->counters_dirty = 1;  // some producers may never arrive
+    if (rc_enq != DECDEC_OK) {
+        c.counters_dirty = 1;  // some producers may never arrive
+        if (forked) {
+            // Join the side stream back so that `stream` (and a capture in progress) is left whole.
+            if (hipEventRecord(c.ev_join, c.side) == hipSuccess) (void)hipStreamWaitEvent(stream, c.ev_join, 0);
+            (void)hipGetLastError();
+        }
+    }
     return rc_enq;
 }
 
-static decdec_linear one_linear(const decdec_desc* d, const void* Wq, const void* scales, const void* zl,
-                                const void* R, const void* Rs, void* y) {
+decdec_linear one_linear(const decdec_desc* d, const void* Wq, const void* scales, const void* zl, const void* R,
+                         const void* Rs, void* y) {
     decdec_linear L;
     L.desc = d;
     L.Wq_dev = Wq;
@@ -558,28 +722,35 @@ static decdec_linear one_linear(const decdec_desc* d, const void* Wq, const void
     return L;
 }
 
+}  // namespace
+
+extern "C" {
+
 int decdec_gemv(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
                 const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev, int32_t k,
                 void* y_f16_dev, decdec_ws* ws, void* stream) {
-    if (d == nullptr) return DECDEC_EINVAL;
+    if (d == nullptr || ws == nullptr) return DECDEC_EINVAL;
     const decdec_linear L =
         one_linear(d, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, y_f16_dev);
-    return gemv_common(1, &L, x_f16_dev, k, nullptr, nullptr, false, ws, stream);
+    return gemv_common(1, &L, x_f16_dev, k, nullptr, nullptr, false, &ws->core, stream);
 }
 
 int decdec_gemv_idx(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
                     const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev, int32_t k,
                     const int32_t* idx_dev, const void* xsel_f16_dev, void* y_f16_dev, decdec_ws* ws, void* stream) {
-    if (d == nullptr) return DECDEC_EINVAL;
+    if (d == nullptr || ws == nullptr) return DECDEC_EINVAL;
     const decdec_linear L =
         one_linear(d, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, y_f16_dev);
-    return gemv_common(1, &L, x_f16_dev, k, idx_dev, xsel_f16_dev, true, ws, stream);
+    return gemv_common(1, &L, x_f16_dev, k, idx_dev, xsel_f16_dev, true, &ws->core, stream);
 }
 
 int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x_f16_dev, int32_t k, decdec_ws* ws,
                       void* stream) {
-    return gemv_common(count, linears, x_f16_dev, k, nullptr, nullptr, false, ws, stream);
+    if (ws == nullptr) return DECDEC_EINVAL;
+    return gemv_common(count, linears, x_f16_dev, k, nullptr, nullptr, false, &ws->core, stream);
 }
+
+// ------------------------------------------------ offline, on the device
 
 int decdec_quantize_uniform(const decdec_desc* d, const void* W_f32_dev, void* Wq_out_dev, void* scales_f16_out_dev,
                             void* zeros_f16_out_dev, void* R_f16_out, void* stream) {

@@ -36,6 +36,7 @@ struct FinalizeArgs {
     const float* cpart;     // [cslices][Ntot]
     unsigned* counters;     // one per tile, zero between calls; null: a separate kernel accumulates
     int gslices, cslices, Ntot;
+    int direct;             // 1: the base GEMV is the only producer and has one slice: it writes y itself
 };
 
 // Store of a partial result that other workgroups (possibly behind another L2) will read.
@@ -52,17 +53,34 @@ __device__ __forceinline__ float load_partial(const float* p) {
 }
 
 // All 64 lanes: add the partial rows of tile nt of matrix m, write y, reset the counter.
+// The summation order of accumulate_kernel: eight interleaved part sums per producer (rows p, p + 8, ...
+// in ascending order), v_p = o_b,p + o_dec,p, combined as a fixed tree.  Rows are loaded eight at a
+// time, all eight requests in flight together; a missing row contributes +0, which leaves a sum that
+// started at +0 unchanged bit for bit.
 __device__ __forceinline__ void finalize_tile(const FinalizeArgs& fa, int m, int nt, int lane) {
     const int cc = fa.col0[m] + nt * 64 + lane;
-    // The summation order of accumulate_kernel: eight interleaved part sums, combined as a fixed tree.
+    float ob[8], odec[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) ob[p] = odec[p] = 0.f;
+    for (int s0 = 0; s0 < fa.gslices; s0 += 8) {
+        float t[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            t[p] = s0 + p < fa.gslices ? load_partial(fa.gpart + (size_t)(s0 + p) * fa.Ntot + cc) : 0.f;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) ob[p] += t[p];
+    }
+    for (int r0 = 0; r0 < fa.cslices; r0 += 8) {
+        float t[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            t[p] = r0 + p < fa.cslices ? load_partial(fa.cpart + (size_t)(r0 + p) * fa.Ntot + cc) : 0.f;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) odec[p] += t[p];
+    }
     float v[8];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        float ob = 0.f, odec = 0.f;
-        for (int s = p; s < fa.gslices; s += 8) ob += load_partial(fa.gpart + (size_t)s * fa.Ntot + cc);
-        for (int r = p; r < fa.cslices; r += 8) odec += load_partial(fa.cpart + (size_t)r * fa.Ntot + cc);
-        v[p] = ob + odec;
-    }
+    for (int p = 0; p < 8; ++p) v[p] = ob[p] + odec[p];
     fa.y[m][nt * 64 + lane] = (_Float16)(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
     if (lane == 0) fa.counters[fa.tile0[m] + nt] = 0;  // ready for the next call (stream-ordered after this one)
 }

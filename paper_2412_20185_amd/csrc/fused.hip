@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kBlockThreads) void compensated_gemv_kernel(
             fetch_int_block<4, SELECT_NCH>(fjobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, cslices, bid);
         }
     } else {
-        gemv_block<KIND, kWavesPerBlock>(gjobs, fa, reinterpret_cast<const uint32_t*>(x), gpart, Ntot, G, gslices, gpw, bid - nfetch);
+        gemv_block<KIND, kWavesPerBlock, 2>(gjobs, fa, reinterpret_cast<const uint32_t*>(x), gpart, Ntot, G, gslices, gpw, bid - nfetch);
     }
 }
 

@@ -7,11 +7,32 @@
 namespace decdec {
 namespace {
 
+template <int KIND, int WPB, int NBUF>
+__global__ __launch_bounds__(WPB * 64) void gemv_kernel(const GemvJobs jobs, const FinalizeArgs fa,
+                                                        const uint32_t* __restrict__ x32, float* __restrict__ part,
+                                                        int Ntot, int G, int slices, int gpw) {
+    gemv_block<KIND, WPB, NBUF>(jobs, fa, x32, part, Ntot, G, slices, gpw, (int)blockIdx.x);
+}
+
+template <int KIND, int WPB>
+hipError_t launch_depth(int nbuf, const KernelTimer* tm, dim3 grid, hipStream_t stream, const GemvJobs& jobs,
+                        const FinalizeArgs& fa, const uint32_t* x32, float* part, int Ntot, int G, int slices, int gpw) {
+    const dim3 block(WPB * 64);
+    if (nbuf >= 4)
+        return launch_kernel(tm, gemv_kernel<KIND, WPB, 4>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G, slices,
+                             gpw);
+    return launch_kernel(tm, gemv_kernel<KIND, WPB, 2>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
+}
+
 template <int KIND>
-__global__ __launch_bounds__(kGemvAloneWaves * 64) void gemv_kernel(const GemvJobs jobs, const FinalizeArgs fa,
-                                                  const uint32_t* __restrict__ x32, float* __restrict__ part,
-                                                  int Ntot, int G, int slices, int gpw) {
-    gemv_block<KIND, kGemvAloneWaves>(jobs, fa, x32, part, Ntot, G, slices, gpw, (int)blockIdx.x);
+hipError_t launch_waves(int wpb, int nbuf, const KernelTimer* tm, dim3 grid, hipStream_t stream, const GemvJobs& jobs,
+                        const FinalizeArgs& fa, const uint32_t* x32, float* part, int Ntot, int G, int slices, int gpw) {
+    switch (wpb) {
+        case 4: return launch_depth<KIND, 4>(nbuf, tm, grid, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
+        case 8: return launch_depth<KIND, 8>(nbuf, tm, grid, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
+        case 16: return launch_depth<KIND, 16>(nbuf, tm, grid, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -35,7 +56,7 @@ int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gp
 }
 
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
-                       int slices, int gpw, const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm) {
+                       int slices, int gpw, int wpb, const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm) {
     const int G = sh.K / kGroup;
     GemvJobs jobs{};
     jobs.n = sh.n;
@@ -49,19 +70,17 @@ hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, c
         tiles += sh.N[m] / kTileCols;
         jobs.tile_end[m] = tiles;
     }
-    const dim3 grid((unsigned)(tiles * slices)), block(kGemvAloneWaves * 64);
+    const dim3 grid((unsigned)(tiles * slices));
     const uint32_t* x32 = static_cast<const uint32_t*>(x);
     const int Ntot = sh.col0[sh.n];
+    const int nbuf = gpw > 2 ? 4 : 2;  // tiles a wave keeps in flight
     switch (kind) {
         case PACK_U4:
-            return launch_kernel(tm, gemv_kernel<PACK_U4>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G, slices,
-                                 gpw);
+            return launch_waves<PACK_U4>(wpb, nbuf, tm, grid, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
         case PACK_U3:
-            return launch_kernel(tm, gemv_kernel<PACK_U3>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G, slices,
-                                 gpw);
+            return launch_waves<PACK_U3>(wpb, nbuf, tm, grid, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
         case PACK_LUT3:
-            return launch_kernel(tm, gemv_kernel<PACK_LUT3>, grid, block, 0, stream, jobs, fa, x32, part, Ntot, G,
-                                 slices, gpw);
+            return launch_waves<PACK_LUT3>(wpb, nbuf, tm, grid, stream, jobs, fa, x32, part, Ntot, G, slices, gpw);
         default:
             return hipErrorInvalidValue;
     }

@@ -216,9 +216,11 @@ struct GemvJobs {
 // Work of workgroup `bid` out of (total tiles) * slices workgroups of WPB wavefronts; workgroup (nt, ks)
 // covers column tile nt (of whichever matrix it falls in) and groups
 // [ks*WPB*gpw, (ks+1)*WPB*gpw), wave w of it the gpw groups starting at
-// (ks*WPB + w)*gpw.  part is fp32 [slices][Ntot].  The loads of the next tile
-// are issued before the current one is consumed.
-template <int KIND, int WPB>
+// (ks*WPB + w)*gpw.  part is fp32 [slices][Ntot].  A wave keeps the loads of
+// NBUF tiles in flight: the tile NBUF groups ahead is requested as soon as the
+// registers of the current one are free.  With fa.direct (one slice, nothing
+// else to add) the workgroup rounds its sums to fp16 and writes y itself.
+template <int KIND, int WPB, int NBUF>
 __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeArgs& fa,
                                            const uint32_t* __restrict__ x32, float* __restrict__ part, int Ntot,
                                            int G, int slices, int gpw, int bid) {
@@ -249,26 +251,55 @@ __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeA
 
     float total = 0.f;
     const uint4* tile = jobs.Wq[m] + ((size_t)nt * G + g) * kTileStride + lane;
-    TileRegs<KIND> ra, rb;
-    if (g < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g, N, n, lane);
-    while (g < g_end) {
-        if (g + 1 < g_end) load_tile<KIND>(rb, tile + kTileStride, scales, zeros_or_lut, x32, g + 1, N, n, lane);
-        total += tile_dot<KIND>(ra, T, x32 + g * 64);
-        if (++g >= g_end) break;
-        tile += 2 * kTileStride;
-        if (g + 1 < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g + 1, N, n, lane);
-        total += tile_dot<KIND>(rb, T, x32 + g * 64);
-        ++g;
+    if constexpr (NBUF == 2) {
+        TileRegs<KIND> ra, rb;
+        if (g < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g, N, n, lane);
+        while (g < g_end) {
+            if (g + 1 < g_end) load_tile<KIND>(rb, tile + kTileStride, scales, zeros_or_lut, x32, g + 1, N, n, lane);
+            total += tile_dot<KIND>(ra, T, x32 + g * 64);
+            if (++g >= g_end) break;
+            tile += 2 * kTileStride;
+            if (g + 1 < g_end) load_tile<KIND>(ra, tile, scales, zeros_or_lut, x32, g + 1, N, n, lane);
+            total += tile_dot<KIND>(rb, T, x32 + g * 64);
+            ++g;
+        }
+    } else {
+        TileRegs<KIND> r[NBUF];
+#pragma unroll
+        for (int i = 0; i < NBUF; ++i)
+            if (g + i < g_end)
+                load_tile<KIND>(r[i], tile + i * kTileStride, scales, zeros_or_lut, x32, g + i, N, n, lane);
+        while (g < g_end) {
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i) {
+                if (g + i >= g_end) break;  // wave-uniform
+                total += tile_dot<KIND>(r[i], T, x32 + (g + i) * 64);
+                if (g + i + NBUF < g_end)
+                    load_tile<KIND>(r[i], tile + (i + NBUF) * kTileStride, scales, zeros_or_lut, x32, g + i + NBUF, N,
+                                    n, lane);
+            }
+            g += NBUF;
+            tile += NBUF * kTileStride;
+        }
     }
 
     red[wave][lane] = total;
     __syncthreads();
     if (wave == 0) {
-        float v = red[0][lane];
+        // a fixed tree over the waves, so that the loads from LDS are independent of one another
+        float v[WPB];
 #pragma unroll
-        for (int w = 1; w < WPB; ++w) v += red[w][lane];
-        store_partial(part + (size_t)ks * Ntot + jobs.col0[m] + n, v, fa.counters != nullptr);
-        if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, m, nt, 1, lane);
+        for (int w = 0; w < WPB; ++w) v[w] = red[w][lane];
+#pragma unroll
+        for (int span = 1; span < WPB; span *= 2)
+#pragma unroll
+            for (int w = 0; w + span < WPB; w += 2 * span) v[w] += v[w + span];
+        if (fa.direct) {
+            fa.y[m][n] = (_Float16)v[0];
+        } else {
+            store_partial(part + (size_t)ks * Ntot + jobs.col0[m] + n, v[0], fa.counters != nullptr);
+            if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, m, nt, 1, lane);
+        }
     }
 }
 

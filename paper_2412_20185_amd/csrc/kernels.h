@@ -64,8 +64,9 @@ struct FetchOperands {
 // gemv.hip ---------------------------------------------------------------
 // part: fp32 [slices][Ntot]; *slices_out receives the number of rows written.
 struct FinalizeArgs;
+// wpb: wavefronts per workgroup (4, 8 or 16).
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
-                       int slices, int gpw, const FinalizeArgs& fa, hipStream_t stream,
+                       int slices, int gpw, int wpb, const FinalizeArgs& fa, hipStream_t stream,
                        const KernelTimer* tm = nullptr);
 // waves_per_block: kGemvAloneWaves for launch_gemv, kWavesPerBlock inside the fused kernel.
 int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gpw_out);

@@ -1,6 +1,8 @@
 """Kernel-level measurements of the library on one MI355X.
 
     python -m paper_2412_20185_amd.microbench gemv     base GEMV kernel per shape: us, GB/s, fraction of 8 TB/s
+    python -m paper_2412_20185_amd.microbench gemvshape  base GEMV launch shapes (waves per workgroup x groups per wave)
+                                                       and the three ways of adding its partial rows
     python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and row split: us, GB/s
     python -m paper_2412_20185_amd.microbench ksweep   latency of a Llama-3-8B layer versus k (4-bit weights),
                                                        next to the knee model of the paper (Section 5.1)
@@ -77,6 +79,70 @@ def gemv(args):
                 print(f"{model:4s} {name:8s} {K:6d} {N:6d} {tag:5s} {nbytes / 1e6:8.2f} {us:10.2f} {gbs:8.0f} "
                       f"{gbs / HBM_PEAK_GBS:9.3f}", flush=True)
                 del Wq
+    ws.close()
+
+
+def gemvshape(args):
+    """Launch shapes of the base GEMV (k = 0): wavefronts per workgroup x groups of 128 input channels per
+    wavefront, with the partial rows added by the accumulate kernel (acc), by the last workgroup of a tile
+    (ink) or not needed at all because one workgroup covers all of K (direct).  Kernel durations from the
+    dispatch timestamps; call = wall time per call over HIP-graph replays of 16 back-to-back calls on
+    rotating weight copies."""
+    import time
+    ws = B.Workspace(28672, 28672, 16)
+    shapes = [("8B", n, K, N) for n, K, N in SHAPES_8B if n != "k/v"] + [("70B", n, K, N) for n, K, N in SHAPES_70B]
+    fmts = {"u3": (3, B.W_UNIFORM_G128), "u4": (4, B.W_UNIFORM_G128), "lut3": (3, B.W_LUT_COL8)}
+    stream = torch.cuda.Stream()
+    print(f"{'model':4s} {'shape':8s} {'fmt':5s} {'waves':>5s} {'gpw':>4s} {'slices':>6s} {'sum':>7s} {'gemv us':>8s} "
+          f"{'acc us':>7s} {'call us':>8s} {'GB/s(gemv)':>10s} {'GB/s(call)':>10s}")
+    for model, name, K, N in shapes:
+        G = K // 128
+        for tag in args.fmts.split(","):
+            bits, wfmt = fmts[tag]
+            d, Wq, sc, zl, nbytes = _operands(K, N, bits, wfmt)
+            x = torch.randn(K, device="cuda").half()
+            y = torch.empty(N, dtype=torch.float16, device="cuda")
+            combos = [(0, 0, 0)]
+            for wpb in (4, 8, 16):
+                for gpw in sorted({1, 2, 4, max(1, G // wpb), max(1, G // (2 * wpb)), max(1, G // (4 * wpb))}):
+                    if gpw * wpb <= G or gpw == 1:
+                        combos.append((wpb, gpw, 0))
+                        if -(-G // (gpw * wpb)) > 1:
+                            combos.append((wpb, gpw, 1))
+            for wpb, gpw, ink in combos:
+                ws.set_gemv_waves(wpb)
+                ws.set_gemv_split(gpw)
+                ws.set_inkernel_accumulate(bool(ink))
+                for i in range(4):
+                    B.decdec_gemv(d, x, Wq[i % len(Wq)], sc, zl, None, None, 0, y, ws)
+                torch.cuda.synchronize()
+                ws.set_profiling(args.reps)
+                for i in range(args.reps):
+                    B.decdec_gemv(d, x, Wq[i % len(Wq)], sc, zl, None, None, 0, y, ws)
+                prof = ws.read_profile()
+                ws.set_profiling(0)
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(16):
+                        B.decdec_gemv(d, x, Wq[i % len(Wq)], sc, zl, None, None, 0, y, ws, stream)
+                for _ in range(3):
+                    g.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.reps):
+                    g.replay()
+                torch.cuda.synchronize()
+                call_us = (time.perf_counter() - t0) * 1e6 / (16 * args.reps)
+                del g
+                us = prof["gemv"][0] * 1e3 / prof["gemv"][1]
+                acc = prof["accumulate"][0] * 1e3 / max(prof["accumulate"][1], 1)
+                eff_wpb = wpb or 4
+                eff_gpw = gpw or max(1, -(-(N // 64) * G // 8192))
+                slices = -(-G // (eff_gpw * eff_wpb))
+                how = "direct" if slices == 1 else ("ink" if ink else "acc")
+                print(f"{model:4s} {name:8s} {tag:5s} {wpb:5d} {gpw:4d} {slices:6d} {how:>7s} {us:8.2f} {acc:7.2f} "
+                      f"{call_us:8.2f} {nbytes / us / 1e3:10.0f} {nbytes / call_us / 1e3:10.0f}", flush=True)
+            del Wq
     ws.close()
 
 
@@ -420,18 +486,19 @@ def tune(args):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=("gemv", "fetch", "ksweep", "select", "rformats", "configs", "tune"))
+    ap.add_argument("what", choices=("gemv", "gemvshape", "fetch", "ksweep", "select", "rformats", "configs", "tune"))
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--xpool", type=int, default=8)
+    ap.add_argument("--fmts", default="u3", help="gemvshape: comma-separated weight formats out of u3,u4,lut3")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    {"gemv": gemv, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "configs": configs, "tune": tune}[args.what](args)
+    {"gemv": gemv, "gemvshape": gemvshape, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "configs": configs, "tune": tune}[args.what](args)
     return 0
 
 

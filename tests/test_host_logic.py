@@ -31,38 +31,45 @@ def test_strerror_and_buffer_size():
     # Section 4.3: 1433 channels need 1433 * (4 + 2) bytes
     assert dd.decdec_sc_buffer_bytes(1433) == 8598
     assert dd.decdec_sc_buffer_bytes(0) == 0
+    # the partial rows of the deterministic accumulate: (64 + 64) rows of maxN floats
+    assert dd.decdec_partial_buffer_bytes(28672) == 128 * 28672 * 4
+    assert dd.decdec_partial_buffer_bytes(0) == 0
 
 
 def test_validation_without_gpu():
     L = dd.lib()
+    P = 1 << 20          # stands for a device pointer: validation fails before anything is read
     bad = [dd.Desc(100, 64, 4), dd.Desc(128, 60, 4), dd.Desc(128, 64, 5), dd.Desc(128, 64, 4, wfmt=7),
            dd.Desc(128, 64, 4, rfmt=4), dd.Desc(0, 64, 4)]
     for d in bad:
         assert dd.decdec_packed_bytes(d) == 0
-        assert L.decdec_gemv(C.byref(d), 1, 1, 1, 1, 1, 1, 0, 1, 1, None) == -1
+        assert L.decdec_gemv(C.byref(d), P, P, P, P, P, P, 0, P, P, None) == -1
     assert dd.decdec_packed_bytes(dd.Desc(128, 64, 4, wfmt=dd.W_LUT_COL8)) == 0     # LUT is 3-bit only
-    assert L.decdec_gemv(C.byref(dd.Desc(128, 64, 4, wfmt=dd.W_LUT_COL8)), 1, 1, 1, 1, 1, 1, 0, 1, 1, None) == -2
+    assert L.decdec_gemv(C.byref(dd.Desc(128, 64, 4, wfmt=dd.W_LUT_COL8)), P, P, P, P, P, P, 0, P, P, None) == -2
     good = dd.Desc(256, 128, 3)
     assert dd.decdec_packed_bytes(good) == 256 * 128 * 3 // 8
     assert dd.decdec_packed_bytes(dd.Desc(256, 128, 4)) == 256 * 128 // 2
-    assert L.decdec_gemv(C.byref(good), None, 1, 1, 1, 1, 1, 0, 1, 1, None) == -1     # null x
-    assert L.decdec_gemv(C.byref(good), 1, 1, 1, 1, 1, 1, 0, 1, None, None) == -1     # null workspace
+    assert L.decdec_gemv(C.byref(good), None, P, P, P, P, P, 0, P, P, None) == -1     # null x
+    assert L.decdec_gemv(C.byref(good), P, P, P, P, P, P, 0, P, None, None) == -1     # null workspace
     # select: K not a multiple of 8, k out of range, null pointers
-    assert L.decdec_select_topk(1, 1001, 3, 1, None, None) == -1
-    assert L.decdec_select_topk(1, 1024, 1025, 1, None, None) == -1
-    assert L.decdec_select_topk(1, 1024, -1, 1, None, None) == -1
-    assert L.decdec_select_topk(None, 1024, 3, 1, None, None) == -1
-    assert L.decdec_select_topk(1, 1024, 3, None, None, None) == -1
-    assert L.decdec_select_topk(1, 131072, 3, 1, None, None) == -1
-    assert L.decdec_select_topk(1, 1024, 0, None, None, None) == 0                   # k = 0 enqueues nothing
+    assert L.decdec_select_topk(P, 1001, 3, P, None, None) == -1
+    assert L.decdec_select_topk(P, 1024, 1025, P, None, None) == -1
+    assert L.decdec_select_topk(P, 1024, -1, P, None, None) == -1
+    assert L.decdec_select_topk(None, 1024, 3, P, None, None) == -1
+    assert L.decdec_select_topk(P, 1024, 3, None, None, None) == -1
+    assert L.decdec_select_topk(P, 131072, 3, P, None, None) == -1
+    assert L.decdec_select_topk(P, 1024, 0, None, None, None) == 0                   # k = 0 enqueues nothing
+    assert L.decdec_select_topk(P + 2, 1024, 0, None, None, None) == -1              # x must be 16-byte aligned
+    assert L.decdec_select_topk(P, 1024, 3, P + 2, None, None) == -1                 # idx must be 4-byte aligned
+    assert L.decdec_select_bucket(P + 8, 2048, 0, C.c_float(2.0), C.c_float(1.0), None, None, None) == -1
     # approximate selector: K not a multiple of 1024, k_chunk out of range, boundaries out of order or NaN
-    assert L.decdec_select_bucket(1, 1000, 3, C.c_float(2.0), C.c_float(1.0), 1, None, None) == -1
-    assert L.decdec_select_bucket(1, 2048, 1025, C.c_float(2.0), C.c_float(1.0), 1, None, None) == -1
-    assert L.decdec_select_bucket(1, 2048, 3, C.c_float(1.0), C.c_float(2.0), 1, None, None) == -1
-    assert L.decdec_select_bucket(1, 2048, 3, C.c_float(float("nan")), C.c_float(1.0), 1, None, None) == -1
-    assert L.decdec_select_bucket(1, 2048, 3, C.c_float(1.0), C.c_float(-1.0), 1, None, None) == -1
-    assert L.decdec_select_bucket(None, 2048, 3, C.c_float(2.0), C.c_float(1.0), 1, None, None) == -1
-    assert L.decdec_select_bucket(1, 2048, 0, C.c_float(2.0), C.c_float(1.0), None, None, None) == 0
+    assert L.decdec_select_bucket(P, 1000, 3, C.c_float(2.0), C.c_float(1.0), P, None, None) == -1
+    assert L.decdec_select_bucket(P, 2048, 1025, C.c_float(2.0), C.c_float(1.0), P, None, None) == -1
+    assert L.decdec_select_bucket(P, 2048, 3, C.c_float(1.0), C.c_float(2.0), P, None, None) == -1
+    assert L.decdec_select_bucket(P, 2048, 3, C.c_float(float("nan")), C.c_float(1.0), P, None, None) == -1
+    assert L.decdec_select_bucket(P, 2048, 3, C.c_float(1.0), C.c_float(-1.0), P, None, None) == -1
+    assert L.decdec_select_bucket(None, 2048, 3, C.c_float(2.0), C.c_float(1.0), P, None, None) == -1
+    assert L.decdec_select_bucket(P, 2048, 0, C.c_float(2.0), C.c_float(1.0), None, None, None) == 0
     # packers
     codes = np.zeros((256, 128), np.uint8)
     codes[3, 5] = 8
