@@ -28,7 +28,7 @@
  *     result.  Pointers are borrowed until that work has run.
  *   - Every function returns a decdec_status (0 = OK, negative = error);
  *     nothing throws, aborts or prints.  A call that fails validation
- *     (EINVAL, EUNSUPPORTED, ENOTPINNED) has enqueued nothing.  A
+ *     (EINVAL, EUNSUPPORTED, ENOTPINNED, ETOOLARGE) has enqueued nothing.  A
  *     call that fails with EHIP (a launch was refused) may have enqueued some
  *     of its kernels already: y is then undefined, the stream stays usable
  *     (in TWO_STREAMS mode the second stream has been joined back) and the
@@ -57,7 +57,8 @@ typedef enum {
     DECDEC_EUNSUPPORTED = -2, /* format / bit-width combination not implemented */
     DECDEC_ENOTPINNED = -3,   /* residual pointer is neither pinned host memory nor device memory */
     DECDEC_EHIP = -4,         /* a HIP runtime call failed; see decdec_last_hip_error */
-    DECDEC_ENOMEM = -5        /* workspace allocation failed */
+    DECDEC_ENOMEM = -5,       /* workspace allocation failed */
+    DECDEC_ETOOLARGE = -6     /* decdec_gemv_static: N or k beyond what its fixed scratch buffer holds */
 } decdec_status;
 
 /* Base-weight formats (what the base GEMV de-quantises).
@@ -317,6 +318,26 @@ typedef struct {
  * matrix m alone. */
 int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x_f16_dev, int32_t k,
                       decdec_ws* ws, void* stream);
+
+/* decdec_gemv for callers that cannot allocate: code running under HIP graph
+ * capture before any workspace exists, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same computation and same kernels as decdec_gemv in its
+ * default mode, but no workspace: the selection buffer and the fp32 partial
+ * rows live in a fixed array in the library's device image (about 8.4 MB, held
+ * by every GPU the library runs on until the process ends).  The call
+ * allocates nothing, on the host or on the device.
+ *   Limits: N <= DECDEC_STATIC_MAX_N, k <= DECDEC_STATIC_MAX_SELECTED;
+ *   beyond them the call returns DECDEC_ETOOLARGE and enqueues nothing.
+ *   Other arguments, results and errors as for decdec_gemv.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams without ordering between them) race.  The first
+ * call on a GPU looks the array's address up; make it outside graph capture. */
+#define DECDEC_STATIC_MAX_N 16384
+#define DECDEC_STATIC_MAX_SELECTED 2048
+int decdec_gemv_static(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
+                       const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
+                       const void* R_pinned, const void* R_scales_f16_dev,
+                       int32_t k, void* y_f16_dev, void* stream);
 
 /* ------------------------------------------------ offline, on the device */
 

@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_pack_residual_int", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
     "decdec_partial_buffer_bytes", "decdec_ws_read_profile_launches", "decdec_ws_forget_pointer",
-    "decdec_ws_pointer_queries",
+    "decdec_ws_pointer_queries", "decdec_gemv_static",
     "decdec_quantize_uniform", "decdec_residual_f32", "decdec_quantize_residual", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned", "decdec_check_residual_pointer",
 )
 
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
     L.decdec_ws_forget_pointer.argtypes = [vp, vp]
     L.decdec_ws_pointer_queries.restype = C.c_int64
     L.decdec_ws_pointer_queries.argtypes = [vp]
+    L.decdec_gemv_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     L.decdec_check_pinned.argtypes = [vp]
     L.decdec_check_residual_pointer.argtypes = [vp]
     L.decdec_ws_create.argtypes = [i32, i32, i32, C.POINTER(vp)]
@@ -144,6 +145,8 @@ def decdec_sc_buffer_bytes(k: int) -> int:
 def decdec_partial_buffer_bytes(maxN: int) -> int:
     return int(lib().decdec_partial_buffer_bytes(maxN))
 
+
+STATIC_MAX_N, STATIC_MAX_SELECTED = 16384, 2048
 
 
 def decdec_check_pinned(t) -> int:
@@ -287,6 +290,12 @@ def decdec_select_bucket(x, K: int, k_chunk: int, b0: float, b15: float, idx_out
 def decdec_gemv(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales, k: int, y, ws: Workspace, stream=None):
     _check(lib().decdec_gemv(C.byref(desc), _ptr(x), _ptr(Wq), _ptr(scales), _ptr(zeros_or_lut), _ptr(R_pinned),
                              _ptr(R_scales), k, _ptr(y), ws.handle, _stream(stream)), "decdec_gemv")
+
+
+def decdec_gemv_static(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales, k: int, y, stream=None):
+    _check(lib().decdec_gemv_static(C.byref(desc), _ptr(x), _ptr(Wq), _ptr(scales), _ptr(zeros_or_lut),
+                                    _ptr(R_pinned), _ptr(R_scales), k, _ptr(y), _stream(stream)),
+           "decdec_gemv_static")
 
 
 def decdec_gemv_idx(desc: Desc, x, Wq, scales, zeros_or_lut, R_pinned, R_scales, k: int, idx, xsel, y,

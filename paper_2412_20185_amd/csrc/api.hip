@@ -159,6 +159,7 @@ const char* decdec_strerror(int status) {
         case DECDEC_ENOTPINNED: return "residual pointer is not GPU-visible pinned host memory";
         case DECDEC_EHIP: return "HIP runtime error";
         case DECDEC_ENOMEM: return "out of memory";
+        case DECDEC_ETOOLARGE: return "problem exceeds the static scratch buffer of decdec_gemv_static";
         default: return "unknown status";
     }
 }
@@ -748,6 +749,76 @@ int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x
                       void* stream) {
     if (ws == nullptr) return DECDEC_EINVAL;
     return gemv_common(count, linears, x_f16_dev, k, nullptr, nullptr, false, &ws->core, stream);
+}
+
+// ------------------------------------------------ the entry point that allocates nothing
+
+}  // extern "C"
+
+namespace {
+
+constexpr size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+constexpr size_t kStIdxOff = 0;
+constexpr size_t kStXselOff = kStIdxOff + round256((size_t)DECDEC_STATIC_MAX_SELECTED * 4);
+constexpr size_t kStCountersOff = kStXselOff + round256((size_t)DECDEC_STATIC_MAX_SELECTED * 2);
+constexpr size_t kStGpartOff = kStCountersOff + round256(((size_t)DECDEC_STATIC_MAX_N / 64 + 1) * 4);
+constexpr size_t kStCpartOff = kStGpartOff + (size_t)kMaxGemvSlices * DECDEC_STATIC_MAX_N * 4;
+constexpr size_t kStaticScratchBytes = kStCpartOff + (size_t)kMaxFetchSlices * DECDEC_STATIC_MAX_N * 4;
+
+constexpr int kMaxDevices = 16;
+struct StaticState {
+    Core core;  // buffers point into this GPU's copy of `scratch`
+    PtrEntry slots[kStaticPointerSlots];
+    bool ready;
+};
+StaticState g_static[kMaxDevices];  // zero-initialised; entry d belongs to GPU d
+std::mutex g_static_mutex;
+
+}  // namespace
+
+// Scratch memory of decdec_gemv_static: the selection buffer, the per-tile counters and the fp32 partial rows
+// of both producers, for problems up to DECDEC_STATIC_MAX_N columns and DECDEC_STATIC_MAX_SELECTED channels.
+// Every GPU the library runs on holds its own copy at its own address until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+extern "C" {
+
+int decdec_gemv_static(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev, const void* scales_f16_dev,
+                       const void* zeros_or_lut_f16_dev, const void* R_pinned, const void* R_scales_f16_dev,
+                       int32_t k, void* y_f16_dev, void* stream) {
+    if (d == nullptr) return DECDEC_EINVAL;
+    int dev = -1;
+    DD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return DECDEC_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticState& st = g_static[dev];
+    if (!st.ready) {
+        // Once per GPU, with that GPU current: the address of its copy of the array.
+        void* ptr = nullptr;
+        DD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) return hip_fail(hipErrorInvalidSymbol);
+        unsigned char* base = static_cast<unsigned char*>(ptr);
+        Core& c = st.core;
+        std::memset(&c, 0, sizeof(c));
+        c.maxK = kSelectMaxK;
+        c.maxN = DECDEC_STATIC_MAX_N;
+        c.maxk = DECDEC_STATIC_MAX_SELECTED;
+        c.idx = reinterpret_cast<int32_t*>(base + kStIdxOff);
+        c.xsel = base + kStXselOff;
+        c.counters = reinterpret_cast<unsigned*>(base + kStCountersOff);
+        c.gpart = reinterpret_cast<float*>(base + kStGpartOff);
+        c.cpart = reinterpret_cast<float*>(base + kStCpartOff);
+        c.ptrs.e = st.slots;
+        c.ptrs.cap = kStaticPointerSlots;
+        c.counters_dirty = 1;  // the first call clears the counters with a fill kernel on its stream
+        st.ready = true;
+    }
+    if (check_desc(d) == DECDEC_OK && (d->N > DECDEC_STATIC_MAX_N || k > DECDEC_STATIC_MAX_SELECTED))
+        return DECDEC_ETOOLARGE;
+    const decdec_linear L =
+        one_linear(d, Wq_dev, scales_f16_dev, zeros_or_lut_f16_dev, R_pinned, R_scales_f16_dev, y_f16_dev);
+    return gemv_common(1, &L, x_f16_dev, k, nullptr, nullptr, false, &st.core, stream);
 }
 
 // ------------------------------------------------ offline, on the device

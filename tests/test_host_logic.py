@@ -34,6 +34,7 @@ def test_strerror_and_buffer_size():
     # the partial rows of the deterministic accumulate: (64 + 64) rows of maxN floats
     assert dd.decdec_partial_buffer_bytes(28672) == 128 * 28672 * 4
     assert dd.decdec_partial_buffer_bytes(0) == 0
+    assert "static" in dd.decdec_strerror(-6)
 
 
 def test_validation_without_gpu():
