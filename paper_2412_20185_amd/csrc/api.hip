@@ -207,6 +207,7 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
     c.maxk = maxk;
     c.ptrs.e = ws->slots;
     c.ptrs.cap = kWsPointerSlots;
+    c.inkernel_accumulate = 1;
     const size_t kk = maxk > 0 ? (size_t)maxk : 1;
     hipError_t e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming);
@@ -626,7 +627,9 @@ int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t 
     int gpw = 1;
     const int wpb = fused ? kWavesPerBlock : c.gemv_wpb > 0 ? c.gemv_wpb : kGemvAloneWaves;
     const int gslices = gemv_slices(tiles, sh.K / kGroup, c.gemv_gpw, wpb, &gpw);
-    const int cslices = k > 0 ? fetch_slices(d0->rfmt, sh, k, c.fetch_split, residuals_in_hbm) : 0;
+    FetchPlan plan{0, 0, 0};
+    if (k > 0) plan = fetch_plan(d0->rfmt, sh, k, c.fetch_split, residuals_in_hbm);
+    const int cslices = plan.slices;
 
     FinalizeArgs fa{};
     int t0 = 0;
@@ -678,10 +681,10 @@ int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t 
             }
             if (fused) {
                 DD_HIP(launch_compensated_gemv(kind, d0->rfmt, sh, gop, fop, x, select_chunks, idx, xsel, k, c.gpart,
-                                               gslices, gpw, c.cpart, cslices, fa, stream, tm[2]));
+                                               gslices, gpw, c.cpart, plan, fa, stream, tm[2]));
                 if (pmask) *pmask |= 4;
             } else {
-                DD_HIP(launch_fetch(d0->rfmt, sh, fop, x, select_chunks, idx, xsel, k, c.cpart, cslices, fa, comp,
+                DD_HIP(launch_fetch(d0->rfmt, sh, fop, x, select_chunks, idx, xsel, k, c.cpart, plan, fa, comp,
                                     tm[2]));
                 if (pmask) *pmask |= 4;
                 if (two_streams) DD_HIP(hipEventRecord(c.ev_join, c.side));
@@ -811,6 +814,7 @@ int decdec_gemv_static(const decdec_desc* d, const void* x_f16_dev, const void* 
         c.cpart = reinterpret_cast<float*>(base + kStCpartOff);
         c.ptrs.e = st.slots;
         c.ptrs.cap = kStaticPointerSlots;
+        c.inkernel_accumulate = 1;
         c.counters_dirty = 1;  // the first call clears the counters with a fill kernel on its stream
         st.ready = true;
     }

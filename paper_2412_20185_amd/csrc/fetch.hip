@@ -7,49 +7,37 @@
 namespace decdec {
 namespace {
 
-template <int SELECT_NCH>
-__global__ __launch_bounds__(kBlockThreads) void fetch_fp16_kernel(const FetchJobs jobs, const FinalizeArgs fa,
-                                                        const uint16_t* __restrict__ x, int32_t* idx_g,
-                                                        uint16_t* xsel_g, int k, int K, int Ntot,
-                                                        float* __restrict__ cpart, int wavecols, int slices) {
-    fetch_fp16_block<SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices, (int)blockIdx.x);
-}
-
 template <int BITS, int SELECT_NCH>
-__global__ __launch_bounds__(kBlockThreads) void fetch_int_kernel(const FetchJobs jobs, const FinalizeArgs fa,
-                                                                 const uint16_t* __restrict__ x, int32_t* idx_g,
-                                                                 uint16_t* xsel_g, int k, int K, int Ntot,
-                                                                 float* __restrict__ cpart, int wavecols,
-                                                                 int slices) {
-    fetch_int_block<BITS, SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, wavecols, slices,
-                                      (int)blockIdx.x);
-}
-
-inline int cols_per_wave(int rfmt) { return fetch_cols_per_wave(rfmt); }
-
-inline int total_wavecols(int rfmt, const MultiShape& sh) {
-    int wc = 0;
-    for (int m = 0; m < sh.n; ++m) wc += (sh.N[m] + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
-    return wc;
+__global__ __launch_bounds__(kBlockThreads) void fetch_kernel(const FetchJobs jobs, const FinalizeArgs fa,
+                                                             const uint16_t* __restrict__ x, int32_t* idx_g,
+                                                             uint16_t* xsel_g, int k, int K, int Ntot,
+                                                             float* __restrict__ cpart, int segments, int slices,
+                                                             int row_waves) {
+    fetch_block<BITS, SELECT_NCH>(jobs, fa, x, idx_g, xsel_g, k, K, Ntot, cpart, segments, slices, row_waves,
+                                  (int)blockIdx.x);
 }
 
 }  // namespace
 
-int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm) {
-    const int wavecols = total_wavecols(rfmt, sh);
-    int slices;
-    if (row_split > 0) {
-        slices = row_split;
-    } else {
-        // Host link: about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight saturate
-        // it.  Rows in device memory: latency bound, so eight times as many wavefronts.
-        const int waves = in_hbm ? 1024 : 128;
-        slices = (waves + wavecols - 1) / wavecols;
-    }
-    if (slices > k) slices = k;
-    if (slices > kMaxFetchSlices) slices = kMaxFetchSlices;
-    if (slices < 1) slices = 1;
-    return slices;
+FetchPlan fetch_plan(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm) {
+    FetchPlan p;
+    const int cpw = fetch_cols_per_wave(rfmt);
+    p.segments = 0;
+    for (int m = 0; m < sh.n; ++m) p.segments += (sh.N[m] + cpw - 1) / cpw;
+    // Host link: about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight saturate it.
+    // Rows in device memory: latency bound, so eight times as many wavefronts.
+    const int waves = in_hbm ? 1024 : 128;
+    int per_segment = (waves + p.segments - 1) / p.segments;  // wavefronts that share the rows of one segment
+    if (per_segment > k) per_segment = k;
+    if (per_segment < 1) per_segment = 1;
+    p.slices = row_split > 0 ? row_split : (per_segment + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (p.slices > kMaxFetchSlices) p.slices = kMaxFetchSlices;
+    if (p.slices > k) p.slices = k;
+    if (p.slices < 1) p.slices = 1;
+    p.row_waves = (per_segment + p.slices - 1) / p.slices;
+    if (p.row_waves > kWavesPerBlock) p.row_waves = kWavesPerBlock;
+    if (p.row_waves < 1) p.row_waves = 1;
+    return p;
 }
 
 int fetch_select_chunks(int K, int k) {
@@ -62,52 +50,41 @@ int fetch_select_chunks(int K, int k) {
 
 template <int NCH>
 static hipError_t launch_fetch_nch(int rfmt, const FetchJobs& jobs, const FinalizeArgs& fa, const uint16_t* x,
-                                   int32_t* idx, uint16_t* xs, int k, int K, int Ntot, float* cpart, int wc,
-                                   int slices, dim3 grid, hipStream_t stream, const KernelTimer* tm) {
+                                   int32_t* idx, uint16_t* xs, int k, int K, int Ntot, float* cpart,
+                                   const FetchPlan& p, hipStream_t stream, const KernelTimer* tm) {
     const unsigned lds = NCH > 0 ? (unsigned)(((size_t)k * 6 + 15) / 16 * 16) : 0u;
-    if (rfmt == 0) {
-        return launch_kernel(tm, fetch_fp16_kernel<NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
-                             Ntot, cpart, wc, slices);
+    const dim3 grid((unsigned)(p.segments * p.slices)), block(kBlockThreads);
+    switch (rfmt) {
+        case 0:
+            return launch_kernel(tm, fetch_kernel<16, NCH>, grid, block, lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
+                                 cpart, p.segments, p.slices, p.row_waves);
+        case 1:
+            return launch_kernel(tm, fetch_kernel<4, NCH>, grid, block, lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
+                                 cpart, p.segments, p.slices, p.row_waves);
+        case 2:
+            return launch_kernel(tm, fetch_kernel<2, NCH>, grid, block, lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
+                                 cpart, p.segments, p.slices, p.row_waves);
+        default:
+            return launch_kernel(tm, fetch_kernel<8, NCH>, grid, block, lds, stream, jobs, fa, x, idx, xs, k, K, Ntot,
+                                 cpart, p.segments, p.slices, p.row_waves);
     }
-    if (rfmt == 1) {
-        return launch_kernel(tm, fetch_int_kernel<4, NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k,
-                             K, Ntot, cpart, wc, slices);
-    }
-    if (rfmt == 2) {
-        return launch_kernel(tm, fetch_int_kernel<2, NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k,
-                             K, Ntot, cpart, wc, slices);
-    }
-    return launch_kernel(tm, fetch_int_kernel<8, NCH>, grid, dim3(kBlockThreads), lds, stream, jobs, fa, x, idx, xs, k, K,
-                         Ntot, cpart, wc, slices);
 }
 
 // select_chunks > 0: the kernel selects for itself from x (and writes the selection to idx / xsel);
 // 0: idx / xsel hold the selection already.
 hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const void* x, int select_chunks,
-                        int32_t* idx, void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
+                        int32_t* idx, void* xsel, int k, float* cpart, const FetchPlan& plan, const FinalizeArgs& fa,
                         hipStream_t stream, const KernelTimer* tm) {
-    FetchJobs jobs{};
-    jobs.n = sh.n;
-    int wc = 0;
-    for (int m = 0; m < sh.n; ++m) {
-        jobs.R[m] = static_cast<const uint4*>(op.R[m]);
-        jobs.Rs[m] = static_cast<const uint16_t*>(op.R_scales[m]);
-        jobs.N[m] = sh.N[m];
-        jobs.col0[m] = sh.col0[m];
-        wc += (sh.N[m] + cols_per_wave(rfmt) - 1) / cols_per_wave(rfmt);
-        jobs.wc_end[m] = wc;
-    }
-    const int tasks = wc * slices;
-    const dim3 grid((unsigned)((tasks + kWavesPerBlock - 1) / kWavesPerBlock));
+    const FetchJobs jobs = make_fetch_jobs(rfmt, sh, op);
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* xs = static_cast<uint16_t*>(xsel);
     const int Ntot = sh.col0[sh.n];
     switch (select_chunks) {
-        case 0: return launch_fetch_nch<0>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
-        case 1: return launch_fetch_nch<1>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
-        case 2: return launch_fetch_nch<2>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
-        case 4: return launch_fetch_nch<4>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
-        case 8: return launch_fetch_nch<8>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, wc, slices, grid, stream, tm);
+        case 0: return launch_fetch_nch<0>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, plan, stream, tm);
+        case 1: return launch_fetch_nch<1>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, plan, stream, tm);
+        case 2: return launch_fetch_nch<2>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, plan, stream, tm);
+        case 4: return launch_fetch_nch<4>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, plan, stream, tm);
+        case 8: return launch_fetch_nch<8>(rfmt, jobs, fa, xp, idx, xs, k, sh.K, Ntot, cpart, plan, stream, tm);
         default: return hipErrorInvalidValue;
     }
 }

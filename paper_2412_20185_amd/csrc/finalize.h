@@ -2,7 +2,8 @@
 // folded into the kernels that produce the two terms.
 //
 // The base GEMV leaves `gslices` fp32 partial rows and the residual kernel
-// `cslices`; every 64-column tile of the output has a counter.  A producer
+// `cslices` (one per workgroup and column segment in both); every 64-column
+// tile of the output has a counter.  A producer
 // that has written its part of a tile increments the tile's counter; whichever
 // producer brings the counter to gslices + cslices adds all partial rows of
 // that tile in a fixed order, rounds once to fp16, writes y and resets the
@@ -85,25 +86,22 @@ __device__ __forceinline__ void finalize_tile(const FinalizeArgs& fa, int m, int
     if (lane == 0) fa.counters[fa.tile0[m] + nt] = 0;  // ready for the next call (stream-ordered after this one)
 }
 
+// One thread: count a producer in on tile nt of matrix m, after the partial rows it contributes to that
+// tile have been performed (store_partial coherent, then s_waitcnt vmcnt(0), then - if other wavefronts of
+// the workgroup stored too - a workgroup barrier).  True for the producer that completes the tile.
+__device__ __forceinline__ bool tile_arrive(const FinalizeArgs& fa, int m, int nt) {
+    const unsigned old =
+        __hip_atomic_fetch_add(&fa.counters[fa.tile0[m] + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return old + 1 == (unsigned)(fa.gslices + fa.cslices);
+}
+
 // Called by all 64 lanes of a wavefront after it has written (store_partial,
-// coherent) its partial row for tiles [nt0, nt0 + ntiles) of matrix m
-// (ntiles <= 64): counts the wave in on each of those tiles and finalizes the
-// tiles it completes.
-__device__ __forceinline__ void tiles_arrive_and_finalize(const FinalizeArgs& fa, int m, int nt0, int ntiles,
-                                                          int lane) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's partial rows have been performed
-    bool last = false;
-    if (lane < ntiles) {
-        const unsigned old = __hip_atomic_fetch_add(&fa.counters[fa.tile0[m] + nt0 + lane], 1u, __ATOMIC_RELAXED,
-                                                    __HIP_MEMORY_SCOPE_AGENT);
-        last = old + 1 == (unsigned)(fa.gslices + fa.cslices);
-    }
-    unsigned long long mask = __ballot(last);
-    while (mask) {
-        const int j = __builtin_ctzll(mask);
-        mask &= mask - 1;
-        finalize_tile(fa, m, nt0 + j, lane);
-    }
+// coherent) its partial row for tile nt of matrix m: counts the wave in and
+// adds the tile up if that completed it.
+__device__ __forceinline__ void wave_arrive_and_finalize(const FinalizeArgs& fa, int m, int nt, int lane) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's partial row has been performed
+    const bool last = lane == 0 ? tile_arrive(fa, m, nt) : false;
+    if (__ballot(last)) finalize_tile(fa, m, nt, lane);
 }
 
 }  // namespace decdec

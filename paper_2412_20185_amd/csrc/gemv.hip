@@ -38,11 +38,18 @@ hipError_t launch_waves(int wpb, int nbuf, const KernelTimer* tm, dim3 grid, hip
 }  // namespace
 
 int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gpw_out) {
-    // One group per wavefront while that keeps the grid within what the chip
-    // holds at once (256 CUs x 32 waves): the whole matrix is then requested in
-    // one go.  Larger problems give every wavefront several groups.
-    const long units = tiles * G;
-    int gpw = gpw_request > 0 ? gpw_request : (int)((units + 8191) / 8192);
+    // Enough workgroups to occupy the chip (about 450: 256 compute units, two workgroups of eight
+    // wavefronts each side by side) and no more K-slices than that takes: every slice beyond the first
+    // is one more partial row to write, to wait for and to add.  With 450 column tiles or more a
+    // workgroup walks all of K and there are no partial rows at all.
+    int gpw = gpw_request;
+    if (gpw <= 0) {
+        long want = (448 + tiles / 2) / tiles;  // K-slices that bring the grid to about 448 workgroups
+        if (want < 1) want = 1;
+        if (want > kMaxGemvSlices) want = kMaxGemvSlices;
+        const long per_slice = (G + want - 1) / want;  // groups one workgroup covers
+        gpw = (int)((per_slice + waves_per_block - 1) / waves_per_block);
+    }
     if (gpw < 1) gpw = 1;
     int per_block = gpw * waves_per_block;
     int slices = (G + per_block - 1) / per_block;

@@ -298,7 +298,7 @@ __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeA
             fa.y[m][n] = (_Float16)v[0];
         } else {
             store_partial(part + (size_t)ks * Ntot + jobs.col0[m] + n, v[0], fa.counters != nullptr);
-            if (fa.counters != nullptr) tiles_arrive_and_finalize(fa, m, nt, 1, lane);
+            if (fa.counters != nullptr) wave_arrive_and_finalize(fa, m, nt, lane);
         }
     }
 }

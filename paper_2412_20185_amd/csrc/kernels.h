@@ -12,11 +12,11 @@ namespace decdec {
 // Workgroup size of the base-GEMV, residual and fused kernels (one wavefront = one unit of work in all of them).
 constexpr int kBlockThreads = 512;
 constexpr int kWavesPerBlock = kBlockThreads / 64;
-// The base GEMV on its own (k = 0) runs fastest with smaller workgroups.
-constexpr int kGemvAloneWaves = 4;
+// Wavefronts per workgroup of the base GEMV when it is a kernel of its own.
+constexpr int kGemvAloneWaves = 8;
 
-constexpr int kMaxGemvSlices = 64;   // fp32 partial rows the base GEMV may write
-constexpr int kMaxFetchSlices = 64;  // fp32 partial rows the residual kernel may write
+constexpr int kMaxGemvSlices = 16;   // fp32 partial rows the base GEMV may write
+constexpr int kMaxFetchSlices = 16;  // fp32 partial rows the residual kernel may write
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectMaxK = 65536;
 
@@ -81,21 +81,27 @@ hipError_t launch_select_bucket(const void* x, int K, int k_chunk, float b0, flo
                                 void* xsel_out, hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // fetch.hip --------------------------------------------------------------
-// cpart: fp32 [slices][Ntot]; row_split: requested slices (0 = automatic); in_hbm: the residual rows are in
-// device memory, not behind the host link.
-int fetch_slices(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm);
+// How the residual kernel is laid out: `segments` column segments (one 16-byte piece per lane and row; all
+// matrices of the call together) x `slices` workgroups per segment; `row_waves` wavefronts of each workgroup
+// share its rows.  cpart is fp32 [slices][Ntot].
+struct FetchPlan {
+    int segments, slices, row_waves;
+};
+// row_split: requested workgroups per segment (0 = automatic); in_hbm: the residual rows are in device
+// memory, not behind the host link.
+FetchPlan fetch_plan(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm);
 // select_chunks (from fetch_select_chunks) > 0: the kernel runs the exact top-k on x itself and writes
 // the selection to idx / xsel; 0: idx / xsel hold the selection already (x is not read).
 int fetch_select_chunks(int K, int k);
 hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const void* x, int select_chunks,
-                        int32_t* idx, void* xsel, int k, float* cpart, int slices, const FinalizeArgs& fa,
+                        int32_t* idx, void* xsel, int k, float* cpart, const FetchPlan& plan, const FinalizeArgs& fa,
                         hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // fused.hip -------------------------------------------------------------
 // Base GEMV and residual kernel in one grid (the fetch workgroups come first).
 hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, const GemvOperands& gop,
                                    const FetchOperands& fop, const void* x, int select_chunks, int32_t* idx, void* xsel,
-                                   int k, float* gpart, int gslices, int gpw, float* cpart, int cslices,
+                                   int k, float* gpart, int gslices, int gpw, float* cpart, const FetchPlan& plan,
                                    const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // accumulate.hip ---------------------------------------------------------

@@ -160,7 +160,7 @@ def fetch(args):
         xs = [torch.randn(K, device="cuda").half() for _ in range(8)]
         y = torch.empty(N, dtype=torch.float16, device="cuda")
         line = f"K {K:5d} N {N:5d} k {k:4d} ({k * N * 2 / 1e6:5.2f} MB):"
-        for sp in (0, 2, 4, 8, 16, 32, 64):
+        for sp in (0, 1, 2, 4, 8, 16):
             ws.set_fetch_split(sp)
             for i in range(3):
                 B.decdec_gemv(d, xs[i % 8], Wq[0], sc, zl, R, None, k, y, ws)
@@ -448,7 +448,7 @@ def tune(args):
            for w, K in {(w, lins[names[0]].K) for _, w, names in order}}
     ws = B.Workspace(14336, 28672, 4096)
     stream = torch.cuda.Stream()
-    splits = (1, 2, 4, 8, 16, 32)
+    splits = (1, 2, 4, 8, 16)
     types = [T.LayerType(t, Kof[t], sum(lins[n].N for n in names), candidates=splits) for t, _, names in order]
     cache = {}
 
@@ -474,7 +474,7 @@ def tune(args):
 
     print("target   row-split cap  split (qkv,o,gu,d)   k_chunk (qkv,o,gu,d)   baseline us  tuned us  slowdown  frozen")
     for target in (0.025, 0.05, 0.1, 0.2, 0.5, 1.0, 2.0, 4.0):
-        r = T.tune(types, measure, target, ntb_max_limit=32, k_chunk_limit=128)
+        r = T.tune(types, measure, target, ntb_max_limit=16, k_chunk_limit=128)
         names = [t for t, _, _ in order]
         print(f"{target * 100:6.1f}%  {r.ntb_max:13d}  {str(tuple(r.ntb[n] for n in names)):19s}  "
               f"{str(tuple(r.k_chunk[n] for n in names)):21s}  {r.baseline:11.1f}  {r.time:8.1f}  {r.slowdown * 100:7.1f}%  "
