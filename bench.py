@@ -5,21 +5,29 @@ One "step" is one pass of the whole hot path over one decoder layer of
 Llama-3-8B shape at batch 1: seven compensated GEMVs (q, k, v, o, gate, up,
 down), each = exact top-k selection of |x|, zero-copy fetch of the selected
 fp16 residual rows from pinned host memory, residual GEMV, 3-bit group-128
-base GEMV and the final accumulate, issued in the layer's dependency order on
-one stream.  Weights are synthetic N(0, 0.02^2), activations N(0,1) with 0.5 %
-outlier channels x U(10,50) at positions redrawn every step, k = 2 % of the
-input channels.  Steps rotate over several distinct layers so that the weights
-come from HBM, not from the 256 MB last-level cache.
+base GEMV and the sum of the two, issued in the layer's dependency order on
+one stream as four calls (q+k+v, o, gate+up, down share their inputs).
+Weights are synthetic N(0, 0.02^2), activations N(0,1) with 0.5 % outlier
+channels x U(10,50) at positions redrawn every step, k = 2 % of the input
+channels.  Steps rotate over several distinct layers so that the weights come
+from HBM, not from the 256 MB last-level cache.
 
-Prints ONE JSON line (see the fields at the bottom).  All inputs are resident
-before the timed region (weights in HBM, residuals in pinned host memory where
-the method keeps them, x in HBM).
+Prints ONE JSON line.  All inputs are resident before the timed region
+(weights in HBM, residuals in pinned host memory where the method keeps them,
+x in HBM).  Besides the headline workload the line carries, timed in the same
+run: the same layer against k, the 4-bit layer against k_chunk with the
+paper's latency model beside it, the paper's residual format at and beyond
+the modelled knee, a Llama-3-70B-shaped layer with codebook weights and a
+32-layer step with 4-bit residuals.
 """
 from __future__ import annotations
 
 import argparse
+import contextlib
 import json
+import math
 import os
+import re
 import sys
 import time
 
@@ -29,35 +37,118 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 LINK_PEAK_GBS = 64.0        # PCIe Gen5 x16, one direction (the box reports 32 GT/s x16)
-# HBM bytes per base-GEMV launch from rocprofv3 --pmc (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain
-# copy kernel of known size gives; profiles/gemv_kernel_hbm_traffic_pmc.md), summed over the four launches of a step
-# of the default workload.  Only valid for that workload; other settings report null.
-PMC_TRAFFIC_BYTES_PER_STEP = 89.08e6 + 1.25e6
+LINK_MEASURED_GBS = 57.5    # what zero-copy reads and hipMemcpy both reach on the box
 K_FRACTION = 0.02
-CPU_STEPS = 24              # steps of layer 0 the oracle is timed on and parity-checked against (about 10 s)
+CPU_STEPS = 32              # steps of layer 0 the oracle is timed on and parity-checked against
 K_SWEEP = (0.001, 0.005, 0.01, 0.05)   # further fractions of K timed for the latency-vs-k list
-CFG = 2                     # workload index used for seeding (the second of the five workloads: one Llama-3-8B-shaped layer)
+KCHUNK_SWEEP = (0, 8, 16, 32, 64, 128)  # channels per 1024: k = 0, 32, ..., 512 per 4096 input channels
+CFG = 2                     # workload index used for seeding (the second of the five workloads)
+ORDER = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
+CALL_NAMES = ["q+k+v", "o", "gate+up", "down"]
+TRAFFIC_PROFILE = os.path.join("profiles", "gemv_kernel_hbm_traffic_pmc.md")
+
+
+def log(msg: str):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def traffic_from_profile():
+    """HBM bytes per base-GEMV launch of the default workload as the committed counter profile states them
+    (a line `hbm_traffic_bytes_per_launch: N`), or None when the file has no such line."""
+    try:
+        text = open(os.path.join(ROOT, TRAFFIC_PROFILE)).read()
+    except OSError:
+        return None
+    m = re.search(r"hbm_traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
+    return float(m.group(1)) if m else None
+
+
+class StepRunner:
+    """Runs step(i, mode) for consecutive i, eagerly or as replays of captured HIP graphs of `gs`
+    consecutive steps each; `period` is the number of distinct steps."""
+
+    def __init__(self, torch, step, gs: int, period: int, use_graph: bool):
+        self.torch, self.step, self.gs, self.period, self.use_graph = torch, step, max(1, gs), period, use_graph
+        self.graphs = {}
+        self.stream = torch.cuda.Stream() if use_graph else None
+
+    def _graph(self, i: int, mode):
+        key = (i % math.lcm(self.period, self.gs), mode)
+        g = self.graphs.get(key)
+        if g is None:
+            g = self.torch.cuda.CUDAGraph()
+            with self.torch.cuda.graph(g, stream=self.stream):
+                for j in range(i, i + self.gs):
+                    self.step(j, mode)
+            self.graphs[key] = g
+        return g
+
+    def run(self, i0: int, n: int, mode):
+        i = i0
+        while i < i0 + n:
+            if self.use_graph and i % self.gs == 0 and i + self.gs <= i0 + n:
+                self._graph(i, mode).replay()
+                i += self.gs
+            else:
+                self.step(i, mode)
+                i += 1
+
+    def timed(self, n: int, mode, warmup: int = 0) -> float:
+        """Milliseconds per step over exactly n steps (n a multiple of gs when graphs are on)."""
+        if self.use_graph:
+            self.run(0, n, mode)                 # capture outside the timed region
+        if warmup:
+            self.run(0, warmup, mode)
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.run(0, n, mode)
+        self.torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    def spread(self, samples: int, mode, span: int):
+        """Graph replays (gs steps each) enqueued back to back with an event between every two: sorted
+        microseconds per step of each replay, as the GPU spent them (the host-side cost of launching a graph
+        is outside, as it is in the timed region, where it overlaps the replay before).  The replays cycle over
+        the first `span` steps (a multiple of gs), the ones the timed region ran."""
+        ev = [self.torch.cuda.Event(enable_timing=True) for _ in range(samples + 1)]
+        starts = [(s * self.gs) % span for s in range(samples)]
+        for i in sorted(set(starts)):            # capture (and warm) outside the timed replays
+            self.run(i, self.gs, mode)
+        self.torch.cuda.synchronize()
+        ev[0].record()
+        for s in range(samples):
+            self.run(starts[s], self.gs, mode)
+            ev[s + 1].record()
+        self.torch.cuda.synchronize()
+        return sorted(ev[s].elapsed_time(ev[s + 1]) * 1e3 / self.gs for s in range(samples))
+
+    def drop(self, mode):
+        for key in [k for k in self.graphs if k[1] == mode]:
+            del self.graphs[key]
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--steps", type=int, default=120)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--layers", type=int, default=12,
                     help="distinct layers rotated over (12 x 89 MB > 1 GB: weights come from HBM, not from the 256 MB L3)")
     ap.add_argument("--xpool", type=int, default=32, help="distinct activation draws rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-k-sweep", action="store_true", help="skip the latency-vs-k passes")
-    ap.add_argument("--no-hbm-residuals", action="store_true",
-                    help="skip the extra pass with the residuals resident in GPU memory")
+    ap.add_argument("--no-extra-configs", action="store_true",
+                    help="skip the 4-bit sweep, the 70B-shaped layer, the 32-layer step and the 4-bit-residual rows")
+    ap.add_argument("--hbm-residuals", action="store_true",
+                    help="add a pass with the residuals resident in GPU memory (not the paper's placement)")
     ap.add_argument("--fetch-split", type=int, default=0)
-    ap.add_argument("--inkernel-accumulate", action="store_true",
-                    help="let the last producer of a tile add the partial rows instead of the accumulate kernel")
+    ap.add_argument("--separate-accumulate", action="store_true",
+                    help="add the partial rows with a kernel of its own instead of inside the producing kernels")
     ap.add_argument("--gemv-split", type=int, default=0, help="groups of 128 input channels per wavefront (0 = built-in)")
     ap.add_argument("--graph", type=int, default=1, help="1: replay the steps as captured HIP graphs")
-    ap.add_argument("--graph-steps", type=int, default=8,
-                    help="consecutive steps captured into one graph (a decoder captures all its layers at once)")
+    ap.add_argument("--graph-steps", type=int, default=0,
+                    help="consecutive steps captured into one graph (0: the largest divisor of --steps up to 10; a "
+                         "decoder captures all its layers at once)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--grouping", choices=("grouped", "separate"), default="grouped",
@@ -74,7 +165,7 @@ def main() -> int:
 
     import workloads
     import paper_2412_20185_amd as dd
-    from paper_2412_20185_amd.layer import LinearGroup, UniformLinear
+    from paper_2412_20185_amd.layer import LinearGroup, UniformLinear, StoredLinear
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -82,130 +173,145 @@ def main() -> int:
     torch.cuda.set_device(0)
     shapes = workloads.LLAMA3_8B_LAYER
     bits = 3
+    gs = args.graph_steps or max(d for d in range(1, 11) if args.steps % d == 0)
+    if not args.graph:
+        gs = 1
+    if args.steps % gs != 0:
+        print("bench.py: --graph-steps must divide --steps (the timed region is exactly --steps steps)", file=sys.stderr)
+        return 2
+    extra = not args.no_extra_configs
+    n4 = min(4, args.layers) if extra else 0     # layers also prepared at 4 bits for the k_chunk sweep
 
     # ---------------------------------------------------------------- set-up
     t_setup = time.time()
-    layers = []
+    layers, layers4 = [], []
     for l in range(args.layers):
-        lins = {}
+        lins, lins4 = {}, {}
         for name, K, N, _ in shapes:
-            lins[name] = UniformLinear(workloads.weights(CFG, l, name, K, N), bits)
+            W = workloads.weights(CFG, l, name, K, N)
+            lins[name] = UniformLinear(W, bits)
+            if l < n4:
+                lins4[name] = UniformLinear(W, 4)
         layers.append(lins)
+        if lins4:
+            layers4.append(lins4)
     inputs = sorted({(w, K) for _, K, _, w in shapes})
     xpool = []
     for s in range(args.xpool):
         xpool.append({w: torch.from_numpy(workloads.x_gauss_outliers(CFG, 0, w, s, K)).cuda() for w, K in inputs})
     ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
     kk = {name: workloads.k_for_fraction(K, K_FRACTION) for name, K, _, _ in shapes}
+    Kof = {name: K for name, K, _, _ in shapes}
     maxK = max(K for _, K, _, _ in shapes)
     maxN = 2 * max(N for _, _, N, _ in shapes)       # room for the concatenated columns of gate + up
-    ws = dd.Workspace(maxK, maxN, max(max(kk.values()), workloads.k_for_fraction(maxK, max(K_SWEEP))))
+    maxk = max(max(kk.values()), workloads.k_for_fraction(maxK, max(K_SWEEP)), workloads.k_for_kchunk(maxK, max(KCHUNK_SWEEP)))
+    ws = dd.Workspace(maxK, maxN, maxk)
     if args.fetch_split:
         ws.set_fetch_split(args.fetch_split)
-    if args.inkernel_accumulate:
-        ws.set_inkernel_accumulate(True)
+    if args.separate_accumulate:
+        ws.set_inkernel_accumulate(False)
     if args.gemv_split:
         ws.set_gemv_split(args.gemv_split)
     setup_s = time.time() - t_setup
+    log(f"set-up of {args.layers} layers done in {setup_s:.1f} s")
 
-    # calls per step, in the layer's dependency order: (input name, k, [GEMV names])
-    if args.grouping == "grouped":
-        order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
-    else:
-        order = [(which, [name]) for name, _, _, which in shapes]
-    groups = [[LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for _, names in order]
-              for lins in layers]
+    # calls per step, in the layer's dependency order: (input name, [GEMV names])
+    order = ORDER if args.grouping == "grouped" else [(which, [name]) for name, _, _, which in shapes]
+    call_names = CALL_NAMES if args.grouping == "grouped" else [n for n, _, _, _ in shapes]
     n_calls = len(order)
-    active = {"groups": groups, "tag": "host"}     # which set of layer buffers the steps use
 
-    Kof = {name: K for name, K, _, _ in shapes}
+    def make_groups(layer_list):
+        return [[LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for _, names in order]
+                for lins in layer_list]
 
-    def step(i: int, compensate=True):
-        """compensate: True = the workload's k (2 %), False = base GEMV only, a float = that fraction of K."""
-        xs = xpool[i % args.xpool]
-        for (which, names), grp in zip(order, active["groups"][i % args.layers]):
-            if compensate is True:
-                k = kk[names[0]]
-            elif compensate is False:
-                k = 0
-            else:
-                k = workloads.k_for_fraction(Kof[names[0]], compensate)
-            grp.gemv(xs[which], k, ws)
+    groups = make_groups(layers)
 
-    graphs = {}
-    cap_stream = torch.cuda.Stream() if args.graph else None
-    gs = max(1, args.graph_steps) if args.graph else 1
+    def k_of(names, mode):
+        """mode: True = the workload's k (2 %), False = base GEMV only, ("frac", f) or ("kchunk", c)."""
+        if mode is True:
+            return kk[names[0]]
+        if mode is False:
+            return 0
+        kind, v = mode
+        return workloads.k_for_fraction(Kof[names[0]], v) if kind == "frac" else workloads.k_for_kchunk(Kof[names[0]], v)
 
-    def run_steps(i0: int, n: int, compensate):
-        """Steps i0 .. i0+n-1, eagerly or as replays of captured graphs of `gs` consecutive steps each
-        (a tail shorter than gs runs eagerly)."""
-        import math
-        i = i0
-        while i < i0 + n:
-            if args.graph and i % gs == 0 and i + gs <= i0 + n:
-                key = (i % math.lcm(args.layers, args.xpool, gs), compensate, active["tag"])
-                g = graphs.get(key)
-                if g is None:
-                    g = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(g, stream=cap_stream):
-                        for j in range(i, i + gs):
-                            step(j, compensate)
-                    graphs[key] = g
-                g.replay()
-                i += gs
-            else:
-                step(i, compensate)
-                i += 1
+    def make_step(group_list):
+        def step(i: int, mode=True):
+            xs = xpool[i % args.xpool]
+            for (which, names), grp in zip(order, group_list[i % len(group_list)]):
+                grp.gemv(xs[which], k_of(names, mode), ws)
+        return step
 
-    def timed(n: int, compensate) -> float:
-        if args.graph:
-            run_steps(0, n, compensate)          # capture outside the timed region
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(0, n, compensate)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / n
+    step = make_step(groups)
+    runner = StepRunner(torch, step, gs, math.lcm(args.layers, args.xpool), bool(args.graph))
 
     # ------------------------------------------------------------ timed region
-    run_steps(0, args.warmup, True)
-    ms_step = timed(args.steps, True)
-    run_steps(0, args.warmup, False)
-    ms_base = timed(args.steps, False)
+    runner.run(0, args.warmup, True)
+    ms_step = runner.timed(args.steps, True)
+    runner.run(0, args.warmup, False)
+    ms_base = runner.timed(args.steps, False)
+    log(f"headline: {ms_step * 1e3:.1f} us per step, base-only {ms_base * 1e3:.1f} us")
 
     # latency against k (the metric is quoted "vs k"): the same steps at other fractions of K
-    vs_k = [{"k_frac": 0.0, "us_per_gemv": round(ms_base * 1e3 / len(shapes), 3), "residual_MB_per_step": 0.0}]
+    vs_k = [{"k_frac": 0.0, "us_per_gemv": round(ms_base * 1e3 / len(shapes), 3), "residual_MB_per_step": 0.0,
+             "added_pct": 0.0}]
     for frac in sorted((set() if args.no_k_sweep else set(K_SWEEP)) | {K_FRACTION}):
         if frac == K_FRACTION:
             ms = ms_step
         else:
-            run_steps(0, min(args.warmup, gs), frac)
-            ms = timed(args.steps, frac)
-            for key in [key for key in graphs if key[1] == frac]:
-                del graphs[key]
+            ms = runner.timed(args.steps, ("frac", frac), warmup=gs)
+            runner.drop(("frac", frac))
         rb = sum(workloads.k_for_fraction(K, frac) * N * 2 for _, K, N, _ in shapes)
         vs_k.append({"k_frac": frac, "us_per_gemv": round(ms * 1e3 / len(shapes), 3),
                      "residual_MB_per_step": round(rb / 1e6, 3),
-                     "link_GBs_whole_step": round(rb / (ms * 1e-3) / 1e9, 2)})
+                     "link_GBs_whole_step": round(rb / (ms * 1e-3) / 1e9, 2),
+                     "added_pct": round(100.0 * (ms / ms_base - 1.0), 1)})
 
-    # spread: the same compensated steps once more, each graph replay (gs steps) timed on its own
-    spread = []
-    for i in range(0, args.steps - gs + 1, gs):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(i, gs, True)
-        torch.cuda.synchronize()
-        spread.append((time.perf_counter() - t0) * 1e6 / gs / len(shapes))
-    spread.sort()
+    # spread: the same compensated steps once more, each graph replay timed on its own
+    n_spread = max(16, args.steps // gs)
+    spread = runner.spread(n_spread, True, args.steps)
+    spread_base = runner.spread(n_spread, False, args.steps)
 
-    # --------------------------------- per-kernel durations over the same steps
-    ws.set_profiling(args.steps * n_calls)
-    for i in range(args.steps):
+    # --------------------------------- per-kernel durations over the same steps (eager, dispatch timestamps)
+    prof_steps = min(args.steps, 96)
+    ws.set_profiling(prof_steps * n_calls)
+    for i in range(prof_steps):
         step(i, True)
-    prof = ws.read_profile()
-    for i in range(args.steps):
+    fetch_launches = ws.read_profile_launches("fetch")
+    for i in range(prof_steps):
         step(i, False)
-    prof_base = ws.read_profile()
+    gemv_launches = ws.read_profile_launches("gemv")
+    acc_us = None
+    if args.separate_accumulate:
+        for i in range(prof_steps):
+            step(i, True)
+        acc_ms, acc_n = ws.read_profile()["accumulate"]
+        acc_us = round(acc_ms * 1e3 / max(acc_n, 1), 3)
     ws.set_profiling(0)
+
+    lin0 = layers[0]
+    call_wbytes = [sum(lin0[n].weight_bytes() for n in names) for _, names in order]
+    call_rbytes = [sum(lin0[n].residual_bytes(kk[n]) for n in names) for _, names in order]
+    gemv_bytes, fetch_bytes = sum(call_wbytes), sum(call_rbytes)
+
+    def per_shape(launches_ms, call_bytes, peak):
+        rows = []
+        for c in range(n_calls):
+            mine = launches_ms[c::n_calls]
+            us = 1e3 * sum(mine) / max(len(mine), 1)
+            K, Ntot = Kof[order[c][1][0]], sum(lin0[n].N for n in order[c][1])
+            gbs = call_bytes[c] / us / 1e3 if us > 0 else 0.0
+            rows.append({"call": call_names[c], "K": K, "N": Ntot, "algorithmic_bytes": call_bytes[c],
+                         "avg_launch_us": round(us, 3), "achieved_GBs": round(gbs, 1), "frac": round(gbs / peak, 4)})
+        return rows
+
+    gemv_shapes = per_shape(gemv_launches, call_wbytes, HBM_PEAK_GBS)
+    fetch_shapes = per_shape(fetch_launches, call_rbytes, LINK_PEAK_GBS)
+    g_us_step = sum(r["avg_launch_us"] for r in gemv_shapes)          # base-GEMV kernel time per step
+    f_us_step = sum(r["avg_launch_us"] for r in fetch_shapes)
+    gemv_gbs = gemv_bytes / g_us_step / 1e3 if g_us_step > 0 else 0.0
+    fetch_gbs = fetch_bytes / f_us_step / 1e3 if f_us_step > 0 else 0.0
+    traffic = traffic_from_profile() if (args.grouping == "grouped" and not args.separate_accumulate) else None
 
     if args.pmc_calibrate:
         # A plain elementwise kernel of known size: reads 256 MiB, writes 256 MiB.  The ratio of its
@@ -216,16 +322,38 @@ def main() -> int:
         torch.cuda.synchronize()
         del a, b
 
-    lin0 = layers[0]
-    gemv_bytes = sum(lin0[name].weight_bytes() for name, _, _, _ in shapes)       # per step
-    fetch_bytes = sum(lin0[name].residual_bytes(kk[name]) for name, _, _, _ in shapes)
-    g_ms, g_n = prof["gemv"]
-    f_ms, f_n = prof["fetch"]
-    s_ms, s_n = prof["select"]
-    gb_ms, gb_n = prof_base["gemv"]
-    gemv_gbs_alone = gemv_bytes * args.steps / (gb_ms * 1e-3) / 1e9 if gb_ms > 0 else 0.0
-    fetch_gbs = fetch_bytes * args.steps / (f_ms * 1e-3) / 1e9 if f_ms > 0 else 0.0
+    # ------------------ cost of the selection inside the compensated kernel: the same call with the selection
+    # supplied (decdec_gemv_idx: nothing is selected in the kernel) against the call that selects for itself
+    select_cost = {}
+    for name in ("o", "down"):
+        lin, K = lin0[name], Kof[name]
+        ksel = workloads.k_for_fraction(K, 0.001)
+        x = xpool[0][dict((n, w) for n, _, _, w in shapes)[name]]
+        reps = 48
+        lin.gemv(x, ksel, ys[name], ws)
+        torch.cuda.synchronize()
+        idx_h, xs_h = ws.read_selection(ksel)
+        idx_d, xs_d = torch.from_numpy(idx_h).cuda(), torch.from_numpy(xs_h).cuda()
+        res = {}
+        for tag in ("selects_in_kernel", "selection_supplied"):
+            ws.set_profiling(reps)
+            for i in range(reps):
+                Wl = layers[i % args.layers][name]
+                if tag == "selects_in_kernel":
+                    Wl.gemv(x, ksel, ys[name], ws)
+                else:
+                    dd.decdec_gemv_idx(Wl.desc, x, Wl.Wq, Wl.scales, Wl.zeros, Wl.R, None, ksel, idx_d, xs_d, ys[name], ws)
+            ms, n = ws.read_profile()["fetch"]
+            ws.set_profiling(0)
+            res[tag] = ms * 1e3 / max(n, 1)
+        select_cost[f"K={K}"] = {"k": ksel, "kernel_us_selecting_in_kernel": round(res["selects_in_kernel"], 3),
+                                 "kernel_us_selection_supplied": round(res["selection_supplied"], 3),
+                                 "selection_us": round(res["selects_in_kernel"] - res["selection_supplied"], 3)}
 
+    def pct(sorted_us, q):
+        return round(sorted_us[int(q * (len(sorted_us) - 1))] / len(shapes), 3)
+
+    added_pct = (ms_step / ms_base - 1.0) * 100.0
     out = {
         "metric": "us per compensated GEMV (batch 1) and % of HBM / host-link roofline",
         "value": round(ms_step * 1e3 / len(shapes), 3),
@@ -249,40 +377,62 @@ def main() -> int:
             "residual_bytes_per_step": fetch_bytes,
             "k": kk,
         },
-        "us_per_gemv_p10_p50_p90": [round(spread[int(q * (len(spread) - 1))], 3) for q in (0.1, 0.5, 0.9)] if spread else None,
+        "us_per_gemv_spread": {"p10": pct(spread, 0.1), "p50": pct(spread, 0.5), "p90": pct(spread, 0.9),
+                               "samples": len(spread), "each": f"one graph replay of {gs} steps between two events, replays enqueued back to back"},
         "base_only_us_per_gemv": round(ms_base * 1e3 / len(shapes), 3),
-        "compensation_added_pct": round((ms_step / ms_base - 1.0) * 100.0, 1),
+        "base_only_ms_per_step": round(ms_base, 5),
+        "base_only_us_per_gemv_spread": {"p10": pct(spread_base, 0.1), "p50": pct(spread_base, 0.5),
+                                         "p90": pct(spread_base, 0.9), "samples": len(spread_base)},
+        "base_only_step_HBM_GBs": round(gemv_bytes / (ms_base * 1e-3) / 1e9, 1),
+        "compensation_added_pct": round(added_pct, 1),
         "roofline": {
-            "kernel": f"gemv_kernel<PACK_U3> (base GEMV, {n_calls} launches per step; timed on the base-only steps of this "
-                      "run: in a compensated step the same device code runs inside compensated_gemv_kernel, whose "
-                      "duration is set by the host link)",
+            "kernel": f"gemv_kernel<PACK_U3> (base GEMV incl. the sum of its K-slices, {n_calls} launches per step; timed on "
+                      "the base-only steps of this run: in a compensated step the same device code runs inside "
+                      "compensated_gemv_kernel, whose duration is set by the host link)",
             "bound": "hbm",
-            "achieved": round(gemv_gbs_alone, 1),
+            "achieved": round(gemv_gbs, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": round(gemv_gbs_alone / HBM_PEAK_GBS, 4),
-            "traffic": round(PMC_TRAFFIC_BYTES_PER_STEP / n_calls) if args.grouping == "grouped" else None,
+            "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
+            "traffic": round(traffic) if traffic else None,
+            "traffic_source": TRAFFIC_PROFILE if traffic else None,
             "algorithmic_bytes_per_launch": round(gemv_bytes / n_calls),
-            "avg_launch_us": round(gb_ms * 1e3 / max(gb_n, 1), 3),
+            "avg_launch_us": round(g_us_step / n_calls, 3),
+            "per_launch_shape": gemv_shapes,
         },
         "link_roofline": {
             "kernel": f"compensated_gemv_kernel<PACK_U3, fp16 rows> (selection + zero-copy residual fetch + residual GEMV "
-                      f"in its first workgroups, base GEMV in the others; {n_calls} launches per step)",
+                      f"in its first workgroups, base GEMV in the others, sum of all partial rows by the last workgroup of "
+                      f"a tile; {n_calls} launches per step)",
             "bound": "host_link",
             "achieved": round(fetch_gbs, 2),
             "peak": LINK_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(fetch_gbs / LINK_PEAK_GBS, 4),
+            "frac_of_measured_link_ceiling": round(fetch_gbs / LINK_MEASURED_GBS, 4),
             "algorithmic_bytes_per_launch": round(fetch_bytes / n_calls),
-            "avg_launch_us": round(f_ms * 1e3 / max(f_n, 1), 3),
+            "avg_launch_us": round(f_us_step / n_calls, 3),
+            "per_launch_shape": fetch_shapes,
         },
         "vs_k": vs_k,
-        "select_avg_us": round(s_ms * 1e3 / max(s_n, 1), 3),
-        "accumulate_avg_us": round(prof["accumulate"][0] * 1e3 / max(prof["accumulate"][1], 1), 3),
+        "selection_in_kernel": select_cost,
+        "accumulate": "inside the producing kernels (last workgroup of a 64-column tile)" if acc_us is None
+                      else f"separate kernel, {acc_us} us per launch",
         "setup_s": round(setup_s, 1),
         "launch": f"hip-graph replay, {gs} steps per graph" if args.graph else "eager",
         "grouping": args.grouping,
         "calls_per_step": n_calls,
+        "targets": {
+            "base_gemv_hbm_frac": {"target": 0.70, "achieved": round(gemv_gbs / HBM_PEAK_GBS, 4),
+                                   "met": bool(gemv_gbs / HBM_PEAK_GBS >= 0.70),
+                                   "note": "four launches of 6.8 - 47.8 MB per step; a launch has a floor of 4 - 5 us "
+                                           "on this GPU, see per_launch_shape and configs.llama3_70b_layer"},
+            "compensation_added_pct_at_k_2pct": {"target": 10.0, "achieved": round(added_pct, 1),
+                                                 "met": bool(added_pct <= 10.0),
+                                                 "note": "8.65 MB per step over a 57.5 GB/s link take 150 us against 36 us for "
+                                                         "the base GEMVs: link-bound by construction at this k, see "
+                                                         "paper_operating_point"},
+        },
     }
 
     # ---------------------------------------------- oracle: parity + CPU baseline
@@ -302,70 +452,240 @@ def main() -> int:
                 sel = ws.read_selection(kk[names[0]])[0]
                 for name in names:
                     gpu[st, name] = (ys[name].cpu().numpy().astype(np.float64), sel)
-        worst, worst_abs, mism, cpu_s = 0.0, 0.0, 0, 0.0
-        import contextlib
-        ctx = threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()
-        with ctx:
-          for name, K, N, which in shapes:
+        worst, worst_abs, mism = 0.0, 0.0, 0
+        cpu_s = {"all": 0.0, "one": 0.0}
+        cores_all = os.cpu_count() or 1
+        for name, K, N, which in shapes:
             W = workloads.weights(CFG, 0, name, K, N)
             codes, s, z = oracle.quantize_uniform(W, bits)                     # offline, not timed
-            R = oracle.residual_fp16(W, oracle.dequantize_uniform(codes, s, z))
-            for st in range(CPU_STEPS):
-                x = xpool[st % args.xpool][which].cpu().numpy()
-                t0 = time.perf_counter()                                       # the decode-step work
-                sc = oracle.topk_abs(x, kk[name])
-                y_ref = oracle.compensated_gemv(oracle.dequantize_uniform(codes, s, z), x, R, sc)
-                cpu_s += time.perf_counter() - t0
-                y_gpu, sel = gpu[st, name]
-                mism += int(not np.array_equal(sc, sel))
-                worst = max(worst, oracle.error_metric(y_gpu, y_ref))
-                worst_abs = max(worst_abs, float(np.max(np.abs(y_gpu - y_ref)) / np.max(np.abs(y_ref))))
-            del W, codes, s, z, R
+            W_hat = oracle.dequantize_uniform(codes, s, z)
+            R = oracle.residual_fp16(W, W_hat)
+            xs_np = [xpool[st % args.xpool][which].cpu().numpy() for st in range(CPU_STEPS)]
+            for tag in ("all", "one"):
+                ctx = (threadpool_limits(limits=1) if (tag == "one" and threadpool_limits) else contextlib.nullcontext())
+                with ctx:
+                    for st in range(CPU_STEPS if tag == "all" else max(1, CPU_STEPS // 4)):
+                        x = xs_np[st]
+                        t0 = time.perf_counter()                                   # the decode-step work
+                        sc = oracle.topk_abs(x, kk[name])
+                        y_ref = oracle.compensated_gemv(W_hat, x, R, sc)
+                        cpu_s[tag] += time.perf_counter() - t0
+                        if tag == "all":
+                            y_gpu, sel = gpu[st, name]
+                            mism += int(not np.array_equal(sc, sel))
+                            worst = max(worst, oracle.error_metric(y_gpu, y_ref))
+                            worst_abs = max(worst_abs, float(np.max(np.abs(y_gpu - y_ref)) / np.max(np.abs(y_ref))))
+            del W, codes, s, z, R, W_hat
         n_checked = len(shapes) * CPU_STEPS
+        n_one = len(shapes) * max(1, CPU_STEPS // 4)
         out["parity"] = {"gemvs_checked": n_checked, "index_mismatches": mism, "max_rel_err": float(f"{worst:.3e}"),
                          "tolerance": 2e-3, "max_abs_err_over_max_abs_y": float(f"{worst_abs:.3e}")}
         out["cpu_baseline"] = {
-            "value": round(cpu_s * 1e6 / n_checked, 1),
+            "value": round(cpu_s["all"] * 1e6 / n_checked, 1),
             "unit": "us",
-            "cores": 1,
+            "cores": cores_all,
             "kind": "oracle",
-            "sample": f"{CPU_STEPS} steps (the 7 GEMVs of layer 0, steps 0-{CPU_STEPS - 1}; {cpu_s:.1f} s of CPU work): top-k, "
-                      "fp64 de-quantisation, fp64 GEMV and compensation, NumPy with BLAS limited to 1 thread",
+            "one_thread_value": round(cpu_s["one"] * 1e6 / n_one, 1),
+            "sample": f"{CPU_STEPS} steps of layer 0 (its 7 GEMVs, steps 0-{CPU_STEPS - 1}; {cpu_s['all']:.1f} s of CPU work "
+                      f"with the BLAS on all {cores_all} host cores; one_thread_value: the first {max(1, CPU_STEPS // 4)} "
+                      f"of those steps with the BLAS limited to 1 thread, {cpu_s['one']:.1f} s): exact top-k, fp64 GEMV over "
+                      "the de-quantised weights and compensation; quantisation and de-quantisation are offline and not timed",
         }
+        log(f"oracle leg done: {cpu_s['all'] + cpu_s['one']:.1f} s timed")
+
     # ------------------------- the same steps with the residuals resident in GPU memory
     # (not the paper's placement: with 288 GB of HBM the residuals of a model fit beside its weights,
     # and the same kernels then read the selected rows from HBM instead of over the host link)
-    if not args.no_hbm_residuals:
+    if args.hbm_residuals:
+        import copy
+        dev_layers = []
         for lins in layers:
-            for lin in lins.values():
-                lin.residual_to_device()
-        active["groups"] = [[LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for _, names in order]
-                            for lins in layers]
-        active["tag"] = "hbm"
-        run_steps(0, args.warmup, True)
-        ms_hbm = timed(args.steps, True)
-        rbytes_layer = sum(K * N * 2 for _, K, N, _ in shapes)
-        hbm_vs_k = []
-        for frac in (0.005, 0.05):
-            run_steps(0, min(args.warmup, gs), frac)
-            hbm_vs_k.append({"k_frac": frac, "us_per_gemv": round(timed(args.steps, frac) * 1e3 / len(shapes), 3)})
-        hbm_vs_k.insert(1, {"k_frac": K_FRACTION, "us_per_gemv": round(ms_hbm * 1e3 / len(shapes), 3)})
-        ws.set_profiling(args.steps * n_calls)
-        for i in range(args.steps):
-            step(i, True)
-        prof_hbm = ws.read_profile()
-        ws.set_profiling(0)
+            d = {}
+            for n, lin in lins.items():
+                c = copy.copy(lin)
+                c.R = lin.R.cuda()
+                d[n] = c
+            dev_layers.append(d)
+        r_hbm = StepRunner(torch, make_step(make_groups(dev_layers)), gs, math.lcm(args.layers, args.xpool), bool(args.graph))
+        ms_hbm = r_hbm.timed(args.steps, True, warmup=args.warmup)
         out["hbm_resident_residuals"] = {
-            "vs_k": hbm_vs_k,
             "us_per_gemv": round(ms_hbm * 1e3 / len(shapes), 3),
             "ms_per_step": round(ms_hbm, 5),
-            "compensated_kernel_avg_us": round(prof_hbm["fetch"][0] * 1e3 / max(prof_hbm["fetch"][1], 1), 3),
-            "accumulate_avg_us": round(prof_hbm["accumulate"][0] * 1e3 / max(prof_hbm["accumulate"][1], 1), 3),
             "added_pct_over_base_only": round(100.0 * (ms_hbm / ms_base - 1.0), 1),
-            "extra_gpu_memory_MB_per_layer": round(rbytes_layer / 1e6, 1),
             "note": "same kernels and k = 2 %, residual rows read from HBM instead of pinned host memory; "
                     "not the paper's placement and not the headline value",
         }
+        del r_hbm, dev_layers
+
+    if extra:
+        out["configs"] = {}
+        base_call_us = [r["avg_launch_us"] for r in gemv_shapes]
+        sel_us = {4096: select_cost["K=4096"]["selection_us"], 14336: select_cost["K=14336"]["selection_us"]}
+
+        # ---- the paper's residual format (Section 4.2: 4-bit codes, one scale per output column) on the same layers,
+        # at the knee the paper's model puts on this machine and at the k_chunk that spends 2 % of the weight bytes
+        r_bw = HBM_PEAK_GBS / LINK_MEASURED_GBS
+        knee = 1024.0 / r_bw * bits / 4.0
+        int4_layers = [{n: StoredLinear.like(lin, rbits=4, seed=17 * li + j) for j, (n, lin) in enumerate(lins.items())}
+                       for li, lins in enumerate(layers)]
+        r4 = StepRunner(torch, make_step(make_groups(int4_layers)), gs, math.lcm(args.layers, args.xpool), bool(args.graph))
+        rows = []
+        for kc in (1, 2, int(knee), 8, 15):
+            ms = r4.timed(args.steps, ("kchunk", kc), warmup=gs)
+            r4.drop(("kchunk", kc))
+            rb = sum(workloads.k_for_kchunk(K, kc) * N // 2 for _, K, N, _ in shapes)
+            rows.append({"k_chunk": kc, "us_per_gemv": round(ms * 1e3 / len(shapes), 3),
+                         "added_pct": round(100.0 * (ms / ms_base - 1.0), 1), "residual_MB_per_step": round(rb / 1e6, 3),
+                         "pct_of_weight_bytes": round(100.0 * rb / gemv_bytes, 2),
+                         "link_GBs_whole_step": round(rb / (ms * 1e-3) / 1e9, 2)})
+        out["paper_operating_point"] = {
+            "what": "the same layers and activations with the paper's residual format (4-bit symmetric codes + fp16 scale per "
+                    "output column; stored codes drawn at random, timing only) against k_chunk = channels per 1024",
+            "knee_model": f"k_chunk* = 1024 / R_bw * (b / 4) with R_bw = {HBM_PEAK_GBS:.0f} / {LINK_MEASURED_GBS} = {r_bw:.0f}, b = 3: "
+                          f"{knee:.1f} (Section 5.1)",
+            "base_only_us_per_gemv": round(ms_base * 1e3 / len(shapes), 3),
+            "rows": rows,
+        }
+        del r4, int4_layers
+        log("4-bit-residual rows done")
+
+        # ---- configs[2]: the same layer shapes at 4 bits, k_chunk sweep, the paper's latency model beside it
+        if layers4:
+            step4 = make_step(make_groups(layers4))
+            r3 = StepRunner(torch, step4, gs, math.lcm(len(layers4), args.xpool), bool(args.graph))
+            ws.set_profiling(prof_steps * n_calls)
+            for i in range(prof_steps):
+                step4(i, False)
+            base4_launch = ws.read_profile_launches("gemv")
+            ws.set_profiling(0)
+            base4_call_us = [1e3 * sum(base4_launch[c::n_calls]) / max(len(base4_launch[c::n_calls]), 1)
+                             for c in range(n_calls)]
+            w4_call = [sum(layers4[0][n].weight_bytes() for n in names) for _, names in order]
+            rows, ms0 = [], None
+            for kc in KCHUNK_SWEEP:
+                mode = ("kchunk", kc) if kc else False
+                ms = r3.timed(args.steps, mode, warmup=gs)
+                r3.drop(mode)
+                ms0 = ms if kc == 0 else ms0
+                rb_call = [sum(workloads.k_for_kchunk(Kof[n], kc) * layers4[0][n].N * 2 for n in names) for _, names in order]
+                # Section 5.1: the compensation hides behind the base GEMV while its transfer is the shorter of
+                # the two.  nominal: both at their published bandwidths; measured: this run's base-GEMV kernels,
+                # the in-kernel selection and the link rate the box delivers.
+                nominal = sum(max(w / (HBM_PEAK_GBS * 1e3), r / (LINK_PEAK_GBS * 1e3)) for w, r in zip(w4_call, rb_call))
+                measured = sum(max(b, (sel_us[Kof[names[0]]] + r / (LINK_MEASURED_GBS * 1e3)) if r else 0.0)
+                               for b, r, (_, names) in zip(base4_call_us, rb_call, order))
+                rows.append({"k_chunk": kc, "k_4096": workloads.k_for_kchunk(4096, kc),
+                             "k_14336": workloads.k_for_kchunk(14336, kc), "us_per_step": round(ms * 1e3, 2),
+                             "us_per_gemv": round(ms * 1e3 / len(shapes), 3), "x_base": round(ms / ms0, 3),
+                             "residual_MB_per_step": round(sum(rb_call) / 1e6, 2),
+                             "link_GBs_whole_step": round(sum(rb_call) / (ms * 1e-3) / 1e9, 2) if kc else 0.0,
+                             "model_nominal_us_per_step": round(nominal, 2),
+                             "model_measured_us_per_step": round(measured, 2)})
+            out["configs"]["llama3_8b_layer_4bit_vs_kchunk"] = {
+                "workload": "configs[2]: the Llama-3-8B layer shapes at 4 bits, fp16 host residuals, k_chunk channels per 1024 "
+                            f"input channels, outlier positions redrawn every step; {len(layers4)} layers rotated",
+                "weight_bytes_per_step": sum(w4_call),
+                "model": "sum over the 4 calls of max(base, transfer): nominal = weight bytes / 8 TB/s against residual bytes / "
+                         "64 GB/s; measured = this run's base-GEMV kernel time against in-kernel selection + residual bytes / "
+                         "57.5 GB/s (kernel times, so without the gaps between launches that the wall time contains)",
+                "rows": rows,
+            }
+            del r3
+            log("4-bit k_chunk sweep done")
+
+    # everything of the headline workload can go now
+    del runner, groups, layers, layers4
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    if extra:
+        from paper_2412_20185_amd.layer import random_layer
+        cases = [
+            ("llama3_70b_layer", "configs[3]: Llama-3-70B-shaped layer, 3-bit codebook weights (8 fp16 entries per output "
+             "column), Student-t activations, fp16 host residuals, k = 1 % of K (81 / 286)",
+             workloads.LLAMA3_70B_LAYER, dd.W_LUT_COL8, 16, 2, lambda K: workloads.k_for_fraction(K, 0.01), 4, {}),
+            ("llama3_8b_32_layer_step", "configs[4]: 32-layer Llama-3-8B-shaped decode step (224 GEMVs), 3-bit group-128 "
+             "weights, Student-t activations with 0.5 % outlier channels x30 redrawn each step, 4-bit host residuals, "
+             "k_chunk = 15 (k = 60 / 210: residual bytes 1.9 % of the weight bytes)",
+             workloads.LLAMA3_8B_LAYER, dd.W_UNIFORM_G128, 4, 32, lambda K: workloads.k_for_kchunk(K, 15), 5,
+             dict(outlier_frac=0.005, outlier_mult=30.0)),
+        ]
+        for key, title, shp, wfmt, rbits, nlayers, kof, cfg, xkw in cases:
+            t0 = time.time()
+            ys2 = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shp}
+            lay = [random_layer(shp, 3, wfmt, rbits, ORDER, ys2, seed=100 * cfg + l) for l in range(nlayers)]
+            Kof2 = {name: K for name, K, _, _ in shp}
+            inputs2 = sorted({(w, K) for _, K, _, w in shp})
+            npool = 8
+            xp2 = [{w: torch.from_numpy(workloads.x_student_t(cfg, 0, w, s, K, **xkw)).cuda() for w, K in inputs2}
+                   for s in range(npool)]
+            ws2 = dd.Workspace(max(K for _, K, _, _ in shp), 2 * max(N for _, _, N, _ in shp), 2048)
+            one_layer = nlayers == 2       # a single layer per step, rotated; else the whole stack is one step
+
+            def step2(i, mode):
+                xs = xp2[i % npool]
+                for l in ([i % nlayers] if one_layer else range(nlayers)):
+                    for (which, names), grp in zip(ORDER, lay[l]):
+                        dd.decdec_gemv_multi(grp, xs[which], kof(Kof2[names[0]]) if mode else 0, ws2)
+
+            steps2 = args.steps if one_layer else max(4, args.steps // 10)
+            gs2 = gs if one_layer else 1
+            r = StepRunner(torch, step2, gs2, math.lcm(nlayers if one_layer else 1, npool), bool(args.graph))
+            ms_c = r.timed(steps2 - steps2 % gs2 or gs2, True, warmup=gs2)
+            ms_b = r.timed(steps2 - steps2 % gs2 or gs2, False, warmup=gs2)
+            per_step_layers = 1 if one_layer else nlayers
+            ngemv = per_step_layers * len(shp)
+            rbytes = per_step_layers * sum(kof(K) * N * rbits // 8 for _, K, N, _ in shp)
+            if wfmt == dd.W_UNIFORM_G128:
+                wbytes = per_step_layers * sum(K * N * 3 // 8 + 4 * N * (K // 128) + 2 * K + 2 * N for _, K, N, _ in shp)
+            else:
+                wbytes = per_step_layers * sum(K * N * 3 // 8 + 16 * N + 2 * K + 2 * N for _, K, N, _ in shp)
+            # base-GEMV kernel time per launch shape (eager pass, dispatch timestamps)
+            nprof = 16 if one_layer else 1
+            ws2.set_profiling(nprof * per_step_layers * len(ORDER))
+            for i in range(nprof):
+                step2(i, False)
+            gl = ws2.read_profile_launches("gemv")
+            ws2.set_profiling(0)
+            shapes_rows = []
+            for c, (_, names) in enumerate(ORDER):
+                mine = gl[c::len(ORDER)]
+                us = 1e3 * sum(mine) / max(len(mine), 1)
+                K = Kof2[names[0]]
+                Nt = sum(N for n, _, N, _ in shp if n in names)
+                b = (K * Nt * 3 // 8 + (4 * Nt * (K // 128) if wfmt == dd.W_UNIFORM_G128 else 16 * Nt) + 2 * K + 2 * Nt)
+                shapes_rows.append({"call": CALL_NAMES[c], "K": K, "N": Nt, "algorithmic_bytes": b,
+                                    "avg_launch_us": round(us, 3), "achieved_GBs": round(b / us / 1e3, 1),
+                                    "frac": round(b / us / 1e3 / HBM_PEAK_GBS, 4)})
+            kern_us = sum(rw["avg_launch_us"] for rw in shapes_rows)
+            out["configs"][key] = {
+                "workload": title + "; stored parameters drawn at random in the library's formats (timing only; parity on these "
+                                    "shapes is covered by the GPU tests)",
+                "gemvs_per_step": ngemv,
+                "steps_timed": steps2 - steps2 % gs2 or gs2,
+                "weight_bytes_per_step": wbytes,
+                "residual_bytes_per_step": rbytes,
+                "residual_pct_of_weight_bytes": round(100.0 * rbytes / wbytes, 2),
+                "ms_per_step": round(ms_c, 5),
+                "us_per_gemv": round(ms_c * 1e3 / ngemv, 3),
+                "base_only_ms_per_step": round(ms_b, 5),
+                "base_only_us_per_gemv": round(ms_b * 1e3 / ngemv, 3),
+                "compensation_added_pct": round(100.0 * (ms_c / ms_b - 1.0), 1),
+                "link_GBs_whole_step": round(rbytes / (ms_c * 1e-3) / 1e9, 2),
+                "base_only_step_HBM_GBs": round(wbytes / (ms_b * 1e-3) / 1e9, 1),
+                "base_gemv_roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "achieved": round(wbytes / per_step_layers / kern_us / 1e3, 1),
+                                       "frac": round(wbytes / per_step_layers / kern_us / 1e3 / HBM_PEAK_GBS, 4),
+                                       "per_launch_shape": shapes_rows},
+                "setup_s": round(time.time() - t0, 1),
+            }
+            ws2.close()
+            del r, lay, xp2, ys2
+            gc.collect()
+            torch.cuda.empty_cache()
+            log(f"{key} done")
+
     ws.close()
     print(json.dumps(out))
     return 0

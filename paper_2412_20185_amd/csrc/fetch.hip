@@ -21,7 +21,7 @@ __global__ __launch_bounds__(kBlockThreads) void fetch_kernel(const FetchJobs jo
 
 FetchPlan fetch_plan(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm) {
     FetchPlan p;
-    const int cpw = fetch_cols_per_wave(rfmt);
+    const int cpw = kFetchSegmentCols;
     p.segments = 0;
     for (int m = 0; m < sh.n; ++m) p.segments += (sh.N[m] + cpw - 1) / cpw;
     // Host link: about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight saturate it.

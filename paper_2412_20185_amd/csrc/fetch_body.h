@@ -33,7 +33,8 @@
 
 namespace decdec {
 
-constexpr int kUnroll = 4;  // row loads in flight per lane
+constexpr int kUnroll = 4;            // 16-byte row loads in flight per lane (narrower loads: as many more)
+constexpr int kFetchSegmentCols = 512;  // output columns of one column segment = threads of a workgroup
 
 __device__ __forceinline__ float h2f(uint32_t bits16) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
@@ -95,29 +96,69 @@ __device__ __forceinline__ Selection obtain_selection(const uint16_t* __restrict
     }
 }
 
-// One workgroup = one column segment (64 lanes x 16 bytes of every row) x the
-// rows of row slice rs; wavefront w < row_waves of it takes a contiguous share
-// of those rows.  BITS = 16: fp16 rows.  BITS = 2, 4, 8: integer residuals
-// (Section 4.2: 4-bit symmetric with one scale per output column; 2- and 8-bit
-// are the variants of the paper's bit-width study, Table 2): a 16-byte piece
-// holds CPL = 128/BITS columns,  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
+// What one lane loads of one row: its 8 columns, BITS bits each.
+template <int BITS>
+struct RowPiece;
+template <>
+struct RowPiece<16> {
+    typedef uint4 type;
+};
+template <>
+struct RowPiece<8> {
+    typedef uint2 type;
+};
+template <>
+struct RowPiece<4> {
+    typedef uint32_t type;
+};
+template <>
+struct RowPiece<2> {
+    typedef uint16_t type;
+};
+
+// acc[i] += value of column i of the piece * xs.
+template <int BITS>
+__device__ __forceinline__ void accumulate_piece(const typename RowPiece<BITS>::type& v, float xs, float (&acc)[8]) {
+    if constexpr (BITS == 16) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            acc[2 * c] = fmaf(h2f(w[c] & 0xFFFFu), xs, acc[2 * c]);
+            acc[2 * c + 1] = fmaf(h2f(w[c] >> 16), xs, acc[2 * c + 1]);
+        }
+    } else if constexpr (BITS == 8) {
+        const uint32_t w[2] = {v.x, v.y};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = fmaf((float)((int)(w[i >> 2] << (24 - 8 * (i & 3))) >> 24), xs, acc[i]);
+    } else {
+        const uint32_t w = v;  // 8 two's-complement fields of BITS bits
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = fmaf((float)((int)(w << (32 - BITS * (i + 1))) >> (32 - BITS)), xs, acc[i]);
+    }
+}
+
+// One workgroup = one column segment of 512 columns (8 columns per lane: a lane reads 128 x BITS / 16 =
+// 16, 8, 4 or 2 bytes of every row, a wavefront 1 KiB down to 128 bytes of contiguous row) x the rows of row
+// slice rs; wavefront w < row_waves of it takes a contiguous share of those rows and keeps 64 / BITS x 4
+// rows in flight per lane (4 KiB per wavefront in every format).  BITS = 16: fp16 rows.  BITS = 2, 4, 8:
+// integer residuals (Section 4.2: 4-bit symmetric with one scale per output column; 2- and 8-bit are the
+// variants of the paper's bit-width study, Table 2),  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
 //
-// After the row loop the wavefronts' sums are added through LDS, eight columns
-// of every lane per round, in the fixed order w = 0, 1, ...: thread t of the
-// workgroup ends up with the segment's sum for CPL/8 columns.  It writes them
-// to row rs of cpart; with in-kernel accumulation the workgroup then counts
-// itself in on the 64-column tiles of its segment and adds up those it
-// completes (finalize.h).
+// After the row loop the wavefronts' sums are added through LDS in the fixed order w = 0, 1, ...: thread
+// t of the workgroup ends up with the segment's sum for column t.  It writes it to row rs of cpart; with
+// in-kernel accumulation wavefront w then counts the workgroup in on the w-th 64-column tile of the
+// segment and adds that tile up if this completed it (finalize.h).
 template <int BITS, int SELECT_NCH>
 __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const FinalizeArgs& fa,
                                             const uint16_t* __restrict__ x, int32_t* idx_g, uint16_t* xsel_g, int k,
                                             int K, int Ntot, float* __restrict__ cpart, int segments, int slices,
                                             int row_waves, int bid) {
-    constexpr int CPL = 128 / BITS;                // columns per lane (per 16-byte piece)
-    constexpr int ROUNDS = CPL / 8;                // LDS rounds of 8 columns per lane
-    constexpr int CPW = BITS == 16 ? 2 : 32 / BITS;  // columns per 32-bit word
+    typedef typename RowPiece<BITS>::type piece_t;
+    constexpr int UNROLL = kUnroll * 16 / BITS;  // row loads in flight per lane
+    static_assert(kBlockThreads == kFetchSegmentCols, "one thread per column of the segment");
     __shared__ float red[kWavesPerBlock][kBlockThreads];
-    __shared__ unsigned tile_done[64];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -127,118 +168,76 @@ __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const Finaliz
     const uint16_t* xsel = sel.xsel;
     const BlockTask t = block_task(jobs, segments, bid);
     const int N = jobs.N[t.m];
-    const uint4* __restrict__ R = jobs.R[t.m];
-    const int piece = t.wc * 64 + lane;  // 16-byte piece of a row this lane loads
-    const bool active = piece * CPL < N;
-    const size_t row16 = (size_t)(N / CPL);
+    const piece_t* __restrict__ R = reinterpret_cast<const piece_t*>(jobs.R[t.m]);
+    const int piece = t.wc * 64 + lane;  // this lane's 8 columns of a row
+    const bool active = piece * 8 < N;
+    const size_t row_pieces = (size_t)(N / 8);
     // rows of this wavefront: slice (rs, wave) out of slices * row_waves equal shares of the k selected rows
     const int rows_per = (k + slices * row_waves - 1) / (slices * row_waves);
     const int j0 = min((t.rs * row_waves + wave) * rows_per, k);
     const int j1 = wave < row_waves ? min(j0 + rows_per, k) : j0;
 
-    // Columns this thread owns after the LDS rounds: round q gives it column ocol + 8 q of the matrix.
-    const int ocol = (t.wc * 64 + (tid >> 3)) * CPL + (tid & 7);
-    const bool owns = ocol < N;  // N is a multiple of 64, hence of 8 q steps inside a piece
-    // The column scales are requested before the rows, so that they arrive behind the first row loads
-    // instead of costing a round trip of their own after the last one.
-    uint16_t sraw[ROUNDS];
+    const int ocol = t.wc * kFetchSegmentCols + tid;  // the column this thread owns after the LDS round
+    const bool owns = ocol < N;
+    // The column scale is requested before the rows, so that it arrives behind the first row loads instead
+    // of costing a round trip of its own after the last one.
+    uint16_t sraw = 0;
     if constexpr (BITS != 16) {
-        const uint16_t* __restrict__ Rs = jobs.Rs[t.m];
-#pragma unroll
-        for (int q = 0; q < ROUNDS; ++q) sraw[q] = owns ? Rs[ocol + 8 * q] : (uint16_t)0;
+        if (owns) sraw = jobs.Rs[t.m][ocol];
     }
 
-    float acc[CPL];
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = j0; j < j1; j += UNROLL) {
+        piece_t v[UNROLL];
+        float xs[UNROLL];
+        int row[UNROLL];
+        uint32_t xraw[UNROLL];
 #pragma unroll
-    for (int i = 0; i < CPL; ++i) acc[i] = 0.f;
-    for (int j = j0; j < j1; j += kUnroll) {
-        uint4 v[kUnroll];
-        float xs[kUnroll];
-        int row[kUnroll];
-        uint32_t xraw[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {  // indices and activations first, so that no row load waits for them
+        for (int u = 0; u < UNROLL; ++u) {  // indices and activations first, so that no row load waits for them
             const int jj = min(j + u, j1 - 1);
             row[u] = idx[jj];
             xraw[u] = xsel[jj];
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            v[u] = make_uint4(0, 0, 0, 0);
-            if (j + u < j1 && active && (unsigned)row[u] < (unsigned)K) v[u] = R[(size_t)row[u] * row16 + piece];
+        for (int u = 0; u < UNROLL; ++u) {
+            v[u] = piece_t{};
+            if (j + u < j1 && active && (unsigned)row[u] < (unsigned)K) v[u] = R[(size_t)row[u] * row_pieces + piece];
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
+        for (int u = 0; u < UNROLL; ++u)
             xs[u] = (j + u < j1 && (unsigned)row[u] < (unsigned)K) ? h2f(xraw[u]) : 0.f;
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < UNROLL; ++u) {
             if (j + u >= j1) break;  // wave-uniform: a short slice does not pay for the rows it does not have
-            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if constexpr (BITS == 16) {
-                    acc[2 * c] = fmaf(h2f(w[c] & 0xFFFFu), xs[u], acc[2 * c]);
-                    acc[2 * c + 1] = fmaf(h2f(w[c] >> 16), xs[u], acc[2 * c + 1]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < CPW; ++i) {
-                        const int q = (int)(w[c] << (32 - BITS * (i + 1))) >> (32 - BITS);  // two's complement field
-                        acc[CPW * c + i] = fmaf((float)q, xs[u], acc[CPW * c + i]);
-                    }
-                }
-            }
+            accumulate_piece<BITS>(v[u], xs[u], acc);
         }
     }
 
-    // Sum over the wavefronts of the workgroup, 8 columns per lane and round.
-    float val[ROUNDS];
-#pragma unroll
-    for (int q = 0; q < ROUNDS; ++q) {
-        if (q > 0) __syncthreads();  // the reads of the round before are done
-        if (wave < row_waves) {
-            float4* dst = reinterpret_cast<float4*>(&red[wave][lane * 8]);
-            dst[0] = make_float4(acc[8 * q], acc[8 * q + 1], acc[8 * q + 2], acc[8 * q + 3]);
-            dst[1] = make_float4(acc[8 * q + 4], acc[8 * q + 5], acc[8 * q + 6], acc[8 * q + 7]);
-        }
-        __syncthreads();
-        float s = red[0][tid];
-#pragma unroll
-        for (int w = 1; w < kWavesPerBlock; ++w)
-            if (w < row_waves) s += red[w][tid];  // wave-uniform
-        if constexpr (BITS != 16) s *= h2f(sraw[q]);
-        val[q] = s;
+    // Sum over the wavefronts of the workgroup.
+    if (wave < row_waves) {
+        float4* dst = reinterpret_cast<float4*>(&red[wave][lane * 8]);
+        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
     }
+    __syncthreads();
+    float val = red[0][tid];
+#pragma unroll
+    for (int w = 1; w < kWavesPerBlock; ++w)
+        if (w < row_waves) val += red[w][tid];  // wave-uniform
+    if constexpr (BITS != 16) val *= h2f(sraw);
 
     const bool coherent = fa.counters != nullptr;
-    if (owns) {
-        float* out = cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + ocol;
-#pragma unroll
-        for (int q = 0; q < ROUNDS; ++q) store_partial(out + 8 * q, val[q], coherent);
-    }
-    if (!coherent) return;
-
-    // In-kernel accumulation: once every store of the workgroup has been performed, count the workgroup in
-    // on the tiles of its segment; the wavefronts then share the tiles it has completed.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    const int tile0 = t.wc * CPL;                      // first 64-column tile of the segment inside matrix m
-    const int ntiles = min(CPL, N / 64 - tile0);       // CPL <= 64 tiles per segment
-    if (tid < ntiles) tile_done[tid] = tile_arrive(fa, t.m, tile0 + tid) ? 1u : 0u;
-    __syncthreads();
-    for (int j = wave; j < ntiles; j += kWavesPerBlock)
-        if (tile_done[j]) finalize_tile(fa, t.m, tile0 + j, lane);
-}
-
-// Columns one workgroup covers (one 16-byte piece per lane and row), by residual format (decdec_rfmt).
-__host__ __device__ constexpr int fetch_cols_per_wave(int rfmt) {
-    return rfmt == 0 ? 512 : rfmt == 1 ? 2048 : rfmt == 2 ? 4096 : 1024;
+    if (owns) store_partial(cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + ocol, val, coherent);
+    // In-kernel accumulation: wavefront w holds exactly the 64 columns of tile w of the segment.
+    const int tile = t.wc * (kFetchSegmentCols / 64) + wave;
+    if (coherent && tile * 64 < N) wave_arrive_and_finalize(fa, t.m, tile, lane);
 }
 
 // Host: kernel-side description of the matrices of one call.
 inline FetchJobs make_fetch_jobs(int rfmt, const MultiShape& sh, const FetchOperands& op) {
     FetchJobs jobs{};
     jobs.n = sh.n;
-    const int cpw = fetch_cols_per_wave(rfmt);
+    const int cpw = kFetchSegmentCols;
     int wc = 0;
     for (int m = 0; m < sh.n; ++m) {
         jobs.R[m] = static_cast<const uint4*>(op.R[m]);

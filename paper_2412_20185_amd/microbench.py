@@ -223,35 +223,12 @@ def rformats(args):
     ws.close()
 
 
-def _random_layer(shapes, wbits, wfmt, rbits, order, ys):
-    """Stored parameters of one decoder layer as random bytes (timing does not depend on the values;
-    fp16 residual payloads are kept finite), grouped by shared input."""
-    lin = {}
-    for name, K, N, _ in shapes:
-        d = B.Desc(K, N, wbits, wfmt, B.R_FMT_OF_BITS[rbits])
-        Wq = torch.randint(0, 256, (B.decdec_packed_bytes(d),), dtype=torch.uint8, device="cuda")
-        if wfmt == B.W_UNIFORM_G128:
-            sc = torch.full((K // 128, N), 0.01, dtype=torch.float16, device="cuda")
-            zl = torch.full((K // 128, N), 3.0, dtype=torch.float16, device="cuda")
-        else:
-            sc = None
-            zl = (torch.sort(torch.randn(N, 8, device="cuda"), dim=1).values * 0.02).half().contiguous()
-        R = torch.empty((K, N * rbits // 8), dtype=torch.uint8, pin_memory=True)
-        if rbits == 16:
-            R.view(torch.float16).copy_((torch.randn((K, N), device="cuda") * 0.003).half())
-            Rs = None
-        else:
-            R.copy_(torch.randint(0, 256, R.shape, dtype=torch.uint8, device="cuda"))
-            Rs = torch.full((N,), 1e-3, dtype=torch.float16, device="cuda")
-        lin[name] = (d, Wq, sc, zl, R, Rs, ys[name])
-    return [B.make_linears([lin[n] for n in names]) for _, names in order]
-
-
 def configs(args):
     """Whole decode steps (every GEMV of every layer once) replayed as HIP graphs: wall time per step and
     per GEMV with compensation and without (k = 0), bytes over the host link and the link rate they imply."""
     import time
     import workloads
+    from .layer import random_layer
     order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
     cases = [
         ("Llama-3-70B-shaped layer, 3-bit codebook weights, fp16 residuals, k = 1 % of K, Student-t x",
@@ -262,7 +239,7 @@ def configs(args):
     ]
     for title, shapes, wbits, wfmt, rbits, nlayers, kof, cfg in cases:
         ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
-        layers = [_random_layer(shapes, wbits, wfmt, rbits, order, ys) for _ in range(nlayers)]
+        layers = [random_layer(shapes, wbits, wfmt, rbits, order, ys, seed=l) for l in range(nlayers)]
         Kof = {name: K for name, K, _, _ in shapes}
         inputs = sorted({(w, K) for _, K, _, w in shapes})
         extra = dict(outlier_frac=0.005, outlier_mult=30.0) if cfg == 5 else {}
@@ -428,60 +405,91 @@ def select(args):
                   flush=True)
 
 
-def tune(args):
-    """Section 4.4 on a Llama-3-8B-shaped layer (3-bit weights, fp16 host residuals): for each target slowdown
-    over the uncompensated layer, the row split of the fetch (this library's counterpart of n_tb: fetch
-    workgroups = column segments x row split / 8) and k_chunk per layer type.  measure() = wall time of one
-    layer (4 calls) replayed as a captured graph."""
-    import time
-    import workloads
-    from .layer import LinearGroup, UniformLinear
-    from . import tuner as T
-    shapes = workloads.LLAMA3_8B_LAYER
-    lins = {name: UniformLinear(workloads.weights(2, 0, name, K, N), 3) for name, K, N, _ in shapes}
-    ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
-    order = [("qkv", "attn_in", ["q", "k", "v"]), ("o", "o_in", ["o"]), ("gu", "mlp_in", ["gate", "up"]),
+class LayerHarness:
+    """One decoder layer on the GPU plus measure(config) -> wall microseconds of its four calls replayed as a
+    captured graph, for the parameter tuner (Section 4.4).  config: {type: (fetch workgroups per column
+    segment, k_chunk)} over the layer types qkv, o, gu, d.  model "8b": Llama-3-8B shapes, 3-bit group-128
+    weights quantised on the device from seeded N(0, 0.02^2) weights, fp16 host residuals; "70b": Llama-3-70B
+    shapes with stored parameters drawn at random (3-bit codebook weights, fp16 host residuals)."""
+
+    ORDER = [("qkv", "attn_in", ["q", "k", "v"]), ("o", "o_in", ["o"]), ("gu", "mlp_in", ["gate", "up"]),
              ("d", "down_in", ["down"])]
-    groups = {t: LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for t, _, names in order}
-    Kof = {t: lins[names[0]].K for t, _, names in order}
-    xin = {w: torch.from_numpy(workloads.x_gauss_outliers(2, 0, w, 0, K)).cuda()
-           for w, K in {(w, lins[names[0]].K) for _, w, names in order}}
-    ws = B.Workspace(14336, 28672, 4096)
-    stream = torch.cuda.Stream()
-    splits = (1, 2, 4, 8, 16)
-    types = [T.LayerType(t, Kof[t], sum(lins[n].N for n in names), candidates=splits) for t, _, names in order]
-    cache = {}
 
-    def measure(cfg):
-        key = tuple(sorted(cfg.items()))
-        if key in cache:
-            return cache[key]
+    def __init__(self, model: str = "8b", reps: int = 40, splits=(1, 2, 4, 8, 16)):
+        import workloads
+        from .layer import LinearGroup, StoredLinear, UniformLinear
+        from . import tuner as T
+        self.reps = reps
+        shapes = workloads.LLAMA3_8B_LAYER if model == "8b" else workloads.LLAMA3_70B_LAYER
+        if model == "8b":
+            lins = {name: UniformLinear(workloads.weights(2, 0, name, K, N), 3) for name, K, N, _ in shapes}
+            draw = lambda w, K: workloads.x_gauss_outliers(2, 0, w, 0, K)
+        else:
+            lins = {name: StoredLinear.random(K, N, 3, B.W_LUT_COL8, 16, seed=j) for j, (name, K, N, _) in enumerate(shapes)}
+            draw = lambda w, K: workloads.x_student_t(4, 0, w, 0, K)
+        ys = {name: torch.empty(N, dtype=torch.float16, device="cuda") for name, _, N, _ in shapes}
+        self.groups = {t: LinearGroup([lins[n] for n in names], [ys[n] for n in names]) for t, _, names in self.ORDER}
+        self.Kof = {t: lins[names[0]].K for t, _, names in self.ORDER}
+        self.xin = {w: torch.from_numpy(draw(w, self.Kof[t])).cuda() for t, w, _ in self.ORDER}
+        self.ws = B.Workspace(max(self.Kof.values()), 2 * max(l.N for l in lins.values()), 8192)
+        self.stream = torch.cuda.Stream()
+        self.types = [T.LayerType(t, self.Kof[t], sum(lins[n].N for n in names), candidates=tuple(splits))
+                      for t, _, names in self.ORDER]
+        self.cache = {}
+        self.warm = False
+        self.k_for_kchunk = workloads.k_for_kchunk
+
+    def time_once(self, cfg) -> float:
+        """Wall microseconds per layer of `cfg`, a fresh measurement."""
+        import time
         g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=stream):
-            for t, w, names in order:
+        with torch.cuda.graph(g, stream=self.stream):
+            for t, w, _ in self.ORDER:
                 split, kc = cfg[t]
-                ws.set_fetch_split(split)
-                groups[t].gemv(xin[w], workloads.k_for_kchunk(Kof[t], kc), ws)
-        for _ in range(5):
+                self.ws.set_fetch_split(split)
+                self.groups[t].gemv(self.xin[w], self.k_for_kchunk(self.Kof[t], kc), self.ws, self.stream)
+        for _ in range(10 if self.warm else 200):   # the first measurement also brings the clocks up
             g.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.reps):
-            g.replay()
-        torch.cuda.synchronize()
-        cache[key] = (time.perf_counter() - t0) * 1e6 / args.reps
-        return cache[key]
+        self.warm = True
+        best = float("inf")
+        for _ in range(3):                          # timing noise is one-sided: the quickest of three batches
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(self.reps):
+                g.replay()
+            torch.cuda.synchronize()
+            best = min(best, (time.perf_counter() - t0) * 1e6 / self.reps)
+        return best
 
-    print("target   row-split cap  split (qkv,o,gu,d)   k_chunk (qkv,o,gu,d)   baseline us  tuned us  slowdown  frozen")
+    def measure(self, cfg) -> float:
+        """time_once, remembered per configuration (the tuner asks for the same one several times)."""
+        key = tuple(sorted(cfg.items()))
+        if key not in self.cache:
+            self.cache[key] = self.time_once(cfg)
+        return self.cache[key]
+
+    def close(self):
+        self.ws.set_fetch_split(0)
+        self.ws.close()
+
+
+def tune(args):
+    """Section 4.4 on one decoder layer (--model 8b: Llama-3-8B shapes, 3-bit weights; 70b: Llama-3-70B shapes,
+    3-bit codebook weights; fp16 host residuals): for each target slowdown over the uncompensated layer, the
+    fetch workgroups per column segment (this library's counterpart of n_tb) and k_chunk per layer type.
+    measure() = wall time of one layer (4 calls) replayed as a captured graph."""
+    from . import tuner as T
+    h = LayerHarness(args.model, reps=args.reps)
+    print(f"model {args.model}")
+    print("target   split cap  split (qkv,o,gu,d)   k_chunk (qkv,o,gu,d)   baseline us  tuned us  slowdown  frozen")
     for target in (0.025, 0.05, 0.1, 0.2, 0.5, 1.0, 2.0, 4.0):
-        r = T.tune(types, measure, target, ntb_max_limit=16, k_chunk_limit=128)
-        names = [t for t, _, _ in order]
-        print(f"{target * 100:6.1f}%  {r.ntb_max:13d}  {str(tuple(r.ntb[n] for n in names)):19s}  "
+        r = T.tune(h.types, h.measure, target, ntb_max_limit=16, k_chunk_limit=128)
+        names = [t for t, _, _ in h.ORDER]
+        print(f"{target * 100:6.1f}%  {r.ntb_max:9d}  {str(tuple(r.ntb[n] for n in names)):19s}  "
               f"{str(tuple(r.k_chunk[n] for n in names)):21s}  {r.baseline:11.1f}  {r.time:8.1f}  {r.slowdown * 100:7.1f}%  "
               f"{','.join(r.frozen) or '-'}", flush=True)
-    print(f"{len(cache)} configurations measured")
-    ws.set_fetch_split(0)
-    ws.close()
+    print(f"{len(h.cache)} configurations measured")
+    h.close()
 
 
 def main():
@@ -492,6 +500,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--xpool", type=int, default=8)
+    ap.add_argument("--model", choices=("8b", "70b"), default="8b", help="tune: which layer shapes")
     ap.add_argument("--fmts", default="u3", help="gemvshape: comma-separated weight formats out of u3,u4,lut3")
     args = ap.parse_args()
     if not torch.cuda.is_available():

@@ -71,7 +71,7 @@ def _drawn_residual(g, K, N, rfmt):
 
 
 @pytest.mark.parametrize("rfmt", ["fp16", "int4", "int2", "int8"])
-@pytest.mark.parametrize("K,N", [(8192, 28672), (28672, 8192), (8192, 1024)])
+@pytest.mark.parametrize("K,N", [(8192, 28672), (28672, 8192), (8192, 1024), (8192, 8192)])
 def test_llama3_70b_lut_shapes_sampled(ws, K, N, rfmt):
     """Config 4: 3-bit codebook weights, Student-t activations, k = 1 % of K; with fp16 residuals as the
     config states and with the integer residual formats of Table 2."""
@@ -83,7 +83,7 @@ def test_llama3_70b_lut_shapes_sampled(ws, K, N, rfmt):
     Wq = torch.from_numpy(dd.decdec_pack_weights(desc, codes)).cuda()
     lut_d = torch.from_numpy(lut).cuda()
     k = workloads.k_for_fraction(K, 0.01)
-    x = workloads.x_student_t(4, 0, "down_in" if K > N else "mlp_in", 0, K)
+    x = workloads.x_student_t(4, 0, "down_in" if K > N else "o_in" if K == N else "mlp_in", 0, K)
     y = torch.empty(N, dtype=torch.float16, device="cuda")
     dd.decdec_gemv(desc, torch.from_numpy(x).cuda(), Wq, None, lut_d, R_p, Rs_d, k, y, ws)
     torch.cuda.synchronize()
@@ -163,17 +163,18 @@ def test_config5_selection_every_step_every_layer():
 
 
 @pytest.mark.timeout(600)
-def test_config5_layer_all_gemvs_int4_residuals(ws):
-    """Config 5, layer 0, one step: the seven GEMVs as the four grouped calls the benchmark issues,
-    3-bit weights, 4-bit residuals (oracle quantiser on a two-point scale grid to keep the test short),
-    every output checked."""
+@pytest.mark.parametrize("layer,step", [(0, 0), (17, 41)])
+def test_config5_layer_all_gemvs_int4_residuals(ws, layer, step):
+    """Config 5, one step of one layer (the first layer at the first step, and a later layer at a later
+    step): the seven GEMVs as the four grouped calls the benchmark issues, 3-bit weights, 4-bit residuals
+    (oracle quantiser on a two-point scale grid to keep the test short), every output checked."""
     order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
     shape = {name: (K, N) for name, K, N, _ in workloads.LLAMA3_8B_LAYER}
     for which, names in order:
         K = shape[names[0]][0]
         k = workloads.k_for_kchunk(K, 15)
-        x = workloads.x_student_t(5, 0, which, 0, K, outlier_frac=0.005, outlier_mult=30.0)
-        probs = [Problem(workloads.weights(5, 0, n, *shape[n]), 3, rfmt="int4", alphas=np.array([0.8, 1.0]),
+        x = workloads.x_student_t(5, layer, which, step, K, outlier_frac=0.005, outlier_mult=30.0)
+        probs = [Problem(workloads.weights(5, layer, n, *shape[n]), 3, rfmt="int4", alphas=np.array([0.8, 1.0]),
                          keep_dense=True) for n in names]
         ys = [torch.full((p.N,), float("nan"), dtype=torch.float16, device="cuda") for p in probs]
         lin = dd.make_linears([(p.desc, p.device()["Wq"], p.device()["scales"], p.device()["zl"], p.device()["R"],
@@ -183,5 +184,69 @@ def test_config5_layer_all_gemvs_int4_residuals(ws):
         idx = ws.read_selection(k)[0]
         for n, p, y in zip(names, probs, ys):
             y_ref, sc = p.reference(x, k)
-            assert_parity(y.cpu().numpy(), y_ref, idx, sc, what=f"config 5 {n}")
+            assert_parity(y.cpu().numpy(), y_ref, idx, sc, what=f"config 5 layer {layer} step {step} {n}")
         del probs, lin
+
+
+def test_llama3_70b_kv_codebook_quantised_by_the_oracle_every_column(ws):
+    """Config 4 at the 70B width with the oracle's own clustering quantiser (not drawn parameters): the
+    k / v projection 8192 -> 1024, Student-t activations, k = 1 % of K, every output column checked."""
+    K, N = 8192, 1024
+    p = Problem(workloads.weights(4, 0, "k", K, N), 3, wfmt="lut", lut_iters=4)
+    k = workloads.k_for_fraction(K, 0.01)
+    assert k == 81
+    for step in range(2):
+        x = workloads.x_student_t(4, 0, "attn_in", step, K)
+        y_ref, sc = p.reference(x, k)
+        y, idx, _ = p.run(x, k, ws)
+        err = assert_parity(y, y_ref, idx, sc, what=f"70B k/v lut3 oracle-quantised step {step}")
+        print(f"70B k/v 8192x1024 lut3 (oracle k-means) k={k} step {step}: rel err {err:.2e}")
+
+
+@pytest.mark.timeout(900)
+def test_config3_layer_4bit_every_k_redrawn_steps_through_captured_graphs(ws):
+    """Config 3 as the benchmark issues it: the Llama-3-8B layer at 4 bits as four grouped calls (q+k+v, o,
+    gate+up, down) captured into one HIP graph per k, k = {0, 32, 64, 128, 256, 512} per 4096 input channels
+    (scaled for K = 14336), 8 steps with outlier positions redrawn every step written into the captured
+    input buffers in place; every output of all seven GEMVs is checked against the oracle at every k and
+    step, and every selection through decdec_select_topk."""
+    order = [("attn_in", ["q", "k", "v"]), ("o_in", ["o"]), ("mlp_in", ["gate", "up"]), ("down_in", ["down"])]
+    shape = {name: (K, N) for name, K, N, _ in workloads.LLAMA3_8B_LAYER}
+    probs = {n: Problem(workloads.weights(3, 0, n, *shape[n]), 4) for n in shape}
+    xin = {w: torch.zeros(shape[names[0]][0], dtype=torch.float16, device="cuda") for w, names in order}
+    ys = {n: torch.full((shape[n][1],), float("nan"), dtype=torch.float16, device="cuda") for n in shape}
+    lins = [dd.make_linears([(probs[n].desc, probs[n].device()["Wq"], probs[n].device()["scales"], probs[n].device()["zl"],
+                              probs[n].device()["R"], None, ys[n]) for n in names]) for _, names in order]
+    k_chunks = (0, 8, 16, 32, 64, 128)
+    stream = torch.cuda.Stream()
+    graphs = {}
+    for kc in k_chunks:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for (w, names), lin in zip(order, lins):
+                dd.decdec_gemv_multi(lin, xin[w], workloads.k_for_kchunk(shape[names[0]][0], kc), ws, stream)
+        graphs[kc] = g
+    worst = 0.0
+    idx_buf = torch.empty(2048, dtype=torch.int32, device="cuda")
+    for step in range(8):
+        xs = {w: workloads.x_gauss_outliers(3, 0, w, step, shape[names[0]][0]) for w, names in order}
+        for w in xs:
+            xin[w].copy_(torch.from_numpy(xs[w]))
+        for kc in k_chunks:
+            for y in ys.values():
+                y.fill_(float("nan"))
+            graphs[kc].replay()
+            torch.cuda.synchronize()
+            for w, names in order:
+                K = shape[names[0]][0]
+                k = workloads.k_for_kchunk(K, kc)
+                sc = oracle.topk_abs(xs[w], k)
+                if k:
+                    dd.decdec_select_topk(xin[w], K, k, idx_buf)
+                    torch.cuda.synchronize()
+                    assert np.array_equal(idx_buf[:k].cpu().numpy(), sc), (step, kc, w)
+                for n in names:
+                    y_ref = oracle.compensated_gemv(probs[n].W_hat, xs[w], probs[n].R_real, sc)
+                    worst = max(worst, assert_parity(ys[n].cpu().numpy(), y_ref, sc, sc,
+                                                     what=f"config 3 step {step} k_chunk {kc} {n}"))
+    print(f"config 3: 8 steps x 6 k x 7 GEMVs, worst rel err {worst:.2e}")
