@@ -624,9 +624,8 @@ int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t 
     // The one-grid kernel is built for fp16 and 4-bit residuals; the other formats take the separate kernels.
     const bool fused = k > 0 && c.mode == DECDEC_MODE_FUSED &&
                        (d0->rfmt == DECDEC_R_FP16 || d0->rfmt == DECDEC_R_INT4_SYM_COL);
-    int gpw = 1;
-    const int wpb = fused ? kWavesPerBlock : c.gemv_wpb > 0 ? c.gemv_wpb : kGemvAloneWaves;
-    const int gslices = gemv_slices(tiles, sh.K / kGroup, c.gemv_gpw, wpb, &gpw);
+    const GemvPlan gp = gemv_plan(tiles, sh.K / kGroup, c.gemv_gpw, fused ? kWavesPerBlock : c.gemv_wpb);
+    const int gpw = gp.gpw, wpb = gp.wpb, gslices = gp.slices;
     FetchPlan plan{0, 0, 0};
     if (k > 0) plan = fetch_plan(d0->rfmt, sh, k, c.fetch_split, residuals_in_hbm);
     const int cslices = plan.slices;

@@ -208,8 +208,7 @@ __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const Finaliz
             xs[u] = (j + u < j1 && (unsigned)row[u] < (unsigned)K) ? h2f(xraw[u]) : 0.f;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            if (j + u >= j1) break;  // wave-uniform: a short slice does not pay for the rows it does not have
-            accumulate_piece<BITS>(v[u], xs[u], acc);
+            if (j + u < j1) accumulate_piece<BITS>(v[u], xs[u], acc);  // wave-uniform: rows it does not have cost nothing
         }
     }
 

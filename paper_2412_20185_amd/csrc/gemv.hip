@@ -37,29 +37,35 @@ hipError_t launch_waves(int wpb, int nbuf, const KernelTimer* tm, dim3 grid, hip
 
 }  // namespace
 
-int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gpw_out) {
-    // Enough workgroups to occupy the chip (about 450: 256 compute units, two workgroups of eight
-    // wavefronts each side by side) and no more K-slices than that takes: every slice beyond the first
-    // is one more partial row to write, to wait for and to add.  With 450 column tiles or more a
-    // workgroup walks all of K and there are no partial rows at all.
-    int gpw = gpw_request;
-    if (gpw <= 0) {
-        long want = (448 + tiles / 2) / tiles;  // K-slices that bring the grid to about 448 workgroups
-        if (want < 1) want = 1;
-        if (want > kMaxGemvSlices) want = kMaxGemvSlices;
-        const long per_slice = (G + want - 1) / want;  // groups one workgroup covers
-        gpw = (int)((per_slice + waves_per_block - 1) / waves_per_block);
+GemvPlan gemv_plan(long tiles, int G, int gpw_request, int wpb_request) {
+    // One or two groups per wavefront, so that a wavefront requests all its weights at once, as long as
+    // the chip holds the wavefronts that makes (256 compute units x 32); then the largest workgroups, which
+    // keep the K-slices few: every slice beyond the first is one more partial row to write, to wait for
+    // and to add, and a workgroup that walks all of K writes y itself.  Matrices beyond that run in several
+    // rounds of workgroups, which smaller workgroups fill more evenly.
+    GemvPlan p;
+    const long units = tiles * G;  // (tile, group) pairs = wavefront iterations
+    p.wpb = wpb_request > 0 ? wpb_request : units <= 16384 ? 16 : 8;
+    if (gpw_request > 0) {
+        p.gpw = gpw_request;
+    } else if (units <= 12288) {
+        p.gpw = 1;
+    } else if (units <= 16384) {
+        p.gpw = 2;
+    } else {
+        p.gpw = (G + 4 * p.wpb - 1) / (4 * p.wpb);  // at most four K-slices
+        if (p.gpw < 2) p.gpw = 2;
     }
-    if (gpw < 1) gpw = 1;
-    int per_block = gpw * waves_per_block;
-    int slices = (G + per_block - 1) / per_block;
-    while (slices > kMaxGemvSlices) {
-        ++gpw;
-        per_block = gpw * waves_per_block;
-        slices = (G + per_block - 1) / per_block;
+    const int gpw_8_slices = (G + 8 * p.wpb - 1) / (8 * p.wpb);  // never more than eight partial rows by choice
+    if (gpw_request <= 0 && p.gpw < gpw_8_slices) p.gpw = gpw_8_slices;
+    int per_block = p.gpw * p.wpb;
+    p.slices = (G + per_block - 1) / per_block;
+    while (p.slices > kMaxGemvSlices) {
+        ++p.gpw;
+        per_block = p.gpw * p.wpb;
+        p.slices = (G + per_block - 1) / per_block;
     }
-    *gpw_out = gpw;
-    return slices;
+    return p;
 }
 
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,

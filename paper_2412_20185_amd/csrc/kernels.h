@@ -12,8 +12,6 @@ namespace decdec {
 // Workgroup size of the base-GEMV, residual and fused kernels (one wavefront = one unit of work in all of them).
 constexpr int kBlockThreads = 512;
 constexpr int kWavesPerBlock = kBlockThreads / 64;
-// Wavefronts per workgroup of the base GEMV when it is a kernel of its own.
-constexpr int kGemvAloneWaves = 8;
 
 constexpr int kMaxGemvSlices = 16;   // fp32 partial rows the base GEMV may write
 constexpr int kMaxFetchSlices = 16;  // fp32 partial rows the residual kernel may write
@@ -68,8 +66,13 @@ struct FinalizeArgs;
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
                        int slices, int gpw, int wpb, const FinalizeArgs& fa, hipStream_t stream,
                        const KernelTimer* tm = nullptr);
-// waves_per_block: kGemvAloneWaves for launch_gemv, kWavesPerBlock inside the fused kernel.
-int gemv_slices(long tiles, int G, int gpw_request, int waves_per_block, int* gpw_out);
+// How K is cut: workgroups of `wpb` wavefronts, each wavefront walking `gpw` groups of 128 input channels,
+// `slices` workgroups (and fp32 partial rows) per 64-column tile.  Requests of 0 leave the choice to the
+// library; inside the one-grid kernel wpb is kWavesPerBlock.
+struct GemvPlan {
+    int wpb, gpw, slices;
+};
+GemvPlan gemv_plan(long tiles, int G, int gpw_request, int wpb_request);
 
 // select.hip -------------------------------------------------------------
 hipError_t launch_select_topk(const void* x, int K, int k, int32_t* idx_out, void* xsel_out, hipStream_t stream,
