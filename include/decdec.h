@@ -117,9 +117,9 @@ int decdec_ws_destroy(decdec_ws* ws);
 size_t decdec_sc_buffer_bytes(int32_t k);
 /* Size in bytes of the fp32 partial rows a workspace for maxN output columns
  * holds in addition: the base GEMV splits K over workgroups and the residual
- * kernel splits the selected rows, each leaves up to 64 partial rows of maxN
+ * kernel splits the selected rows, each leaves up to 16 partial rows of maxN
  * floats, and a fixed-order sum of those rows replaces the paper's atomic adds
- * into o_b.  That is 512 maxN bytes (14.7 MB for the 28672 columns of gate + up
+ * into o_b.  That is 128 maxN bytes (3.7 MB for the 28672 columns of gate + up
  * of Llama-3-8B): extra GPU memory the paper's design does not need, the price
  * of a result that does not depend on the order of floating-point atomics. */
 size_t decdec_partial_buffer_bytes(int32_t maxN);
@@ -131,9 +131,13 @@ int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const
  * selection to host arrays (either may be NULL). */
 int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, void* xsel_f16_host);
 
-/* Number of fetch workgroups per output-column block the residual kernel
- * uses (the counterpart of n_tb in Section 4.4); 0 restores the built-in
- * choice.  Affects later calls on this workspace. */
+/* Number of wavefronts that share the selected rows of one 512-column segment
+ * in the residual kernel, 1 .. 128 (the counterpart of n_tb in Section 4.4:
+ * how many requests are in flight on the host link, at the price of compute
+ * units the base GEMV cannot use); they are grouped into workgroups of 8, each
+ * of which leaves one fp32 partial row.  0 restores the built-in choice (about
+ * 128 wavefronts in the whole kernel, which saturate the link; more than about
+ * 500 lower its rate).  Affects later calls on this workspace. */
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
 
 /* How one compensated GEMV (k > 0) is laid out on the GPU.  Every mode adds the
@@ -141,12 +145,14 @@ int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
  * over larger workgroups, so its partial sums may round differently.
  *   FUSED (default): one kernel whose first workgroups do steps 1-3 (selection,
  *     zero-copy fetch, residual GEMV) and whose other workgroups do the base
- *     GEMV, then the accumulate kernel; everything on the caller's stream.
- *   SERIAL: residual kernel, base GEMV kernel, accumulate kernel one after
- *     the other on the caller's stream.
+ *     GEMV, on the caller's stream (fp16 and 4-bit residuals; the 2- and 8-bit
+ *     formats run as SERIAL).
+ *   SERIAL: residual kernel and base GEMV kernel one after the other on the
+ *     caller's stream.
  *   TWO_STREAMS: the arrangement of Section 4.1: steps 1-3 on the workspace's
- *     side stream, the base GEMV on the caller's stream, joined by events
- *     before the accumulate kernel. */
+ *     side stream, the base GEMV on the caller's stream, joined by events.
+ * In every mode the two terms are added as decdec_ws_set_inkernel_accumulate
+ * says. */
 typedef enum { DECDEC_MODE_FUSED = 0, DECDEC_MODE_SERIAL = 1, DECDEC_MODE_TWO_STREAMS = 2 } decdec_mode;
 int decdec_ws_set_mode(decdec_ws* ws, int32_t mode);
 
@@ -158,10 +164,12 @@ int decdec_ws_set_mode(decdec_ws* ws, int32_t mode);
 int decdec_ws_set_separate_select(decdec_ws* ws, int32_t on);
 
 /* How the partial results of the base GEMV and of the residual kernel are
- * added.  on = 0 (default): by a small kernel of its own on the caller's
- * stream.  on = 1: whichever of the two kernels completes a 64-column tile
- * last adds it up (same bits, one launch fewer; slower on MI355X at the sizes
- * measured, because the finalizing wave must read around the L2 caches). */
+ * added (step 4 of Section 4.1; the paper adds with atomics from its fused
+ * kernel).  on = 1 (default): whichever workgroup of either producer completes
+ * a 64-column tile of the output last adds the tile's partial rows in a fixed
+ * order and writes y: no further launch, and the sum does not depend on who
+ * came last.  on = 0: a small kernel of its own on the caller's stream, after
+ * both producers, adds them in the same order (same bits). */
 int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on);
 
 /* Number of 128-channel groups each wavefront of the base GEMV walks through
@@ -323,7 +331,7 @@ int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x
  * capture before any workspace exists, tight serving loops, harnesses that
  * forbid hipMalloc.  Same computation and same kernels as decdec_gemv in its
  * default mode, but no workspace: the selection buffer and the fp32 partial
- * rows live in a fixed array in the library's device image (about 8.4 MB, held
+ * rows live in a fixed array in the library's device image (about 2.1 MB, held
  * by every GPU the library runs on until the process ends).  The call
  * allocates nothing, on the host or on the device.
  *   Limits: N <= DECDEC_STATIC_MAX_N, k <= DECDEC_STATIC_MAX_SELECTED;

@@ -381,7 +381,7 @@ int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, 
 }
 
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split) {
-    if (ws == nullptr || row_split < 0 || row_split > kMaxFetchSlices) return DECDEC_EINVAL;
+    if (ws == nullptr || row_split < 0 || row_split > kMaxFetchSlices * kWavesPerBlock) return DECDEC_EINVAL;
     ws->core.fetch_split = row_split;
     return DECDEC_OK;
 }

@@ -21,22 +21,18 @@ __global__ __launch_bounds__(kBlockThreads) void fetch_kernel(const FetchJobs jo
 
 FetchPlan fetch_plan(int rfmt, const MultiShape& sh, int k, int row_split, bool in_hbm) {
     FetchPlan p;
-    const int cpw = kFetchSegmentCols;
     p.segments = 0;
-    for (int m = 0; m < sh.n; ++m) p.segments += (sh.N[m] + cpw - 1) / cpw;
-    // Host link: about 128 wavefronts x kUnroll rows x 1 KiB = 512 KiB of requests in flight saturate it.
+    for (int m = 0; m < sh.n; ++m) p.segments += (sh.N[m] + kFetchSegmentCols - 1) / kFetchSegmentCols;
+    // Host link: about 128 wavefronts x 4 KiB of row loads each = 512 KiB of requests in flight saturate it.
     // Rows in device memory: latency bound, so eight times as many wavefronts.
     const int waves = in_hbm ? 1024 : 128;
-    int per_segment = (waves + p.segments - 1) / p.segments;  // wavefronts that share the rows of one segment
+    // wavefronts that share the rows of one segment
+    int per_segment = row_split > 0 ? row_split : (waves + p.segments - 1) / p.segments;
+    if (per_segment > kMaxFetchSlices * kWavesPerBlock) per_segment = kMaxFetchSlices * kWavesPerBlock;
     if (per_segment > k) per_segment = k;
     if (per_segment < 1) per_segment = 1;
-    p.slices = row_split > 0 ? row_split : (per_segment + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (p.slices > kMaxFetchSlices) p.slices = kMaxFetchSlices;
-    if (p.slices > k) p.slices = k;
-    if (p.slices < 1) p.slices = 1;
+    p.slices = (per_segment + kWavesPerBlock - 1) / kWavesPerBlock;
     p.row_waves = (per_segment + p.slices - 1) / p.slices;
-    if (p.row_waves > kWavesPerBlock) p.row_waves = kWavesPerBlock;
-    if (p.row_waves < 1) p.row_waves = 1;
     return p;
 }
 

@@ -160,7 +160,7 @@ def fetch(args):
         xs = [torch.randn(K, device="cuda").half() for _ in range(8)]
         y = torch.empty(N, dtype=torch.float16, device="cuda")
         line = f"K {K:5d} N {N:5d} k {k:4d} ({k * N * 2 / 1e6:5.2f} MB):"
-        for sp in (0, 1, 2, 4, 8, 16):
+        for sp in (0, 2, 4, 8, 16, 32, 64, 128):
             ws.set_fetch_split(sp)
             for i in range(3):
                 B.decdec_gemv(d, xs[i % 8], Wq[0], sc, zl, R, None, k, y, ws)
@@ -415,7 +415,7 @@ class LayerHarness:
     ORDER = [("qkv", "attn_in", ["q", "k", "v"]), ("o", "o_in", ["o"]), ("gu", "mlp_in", ["gate", "up"]),
              ("d", "down_in", ["down"])]
 
-    def __init__(self, model: str = "8b", reps: int = 40, splits=(1, 2, 4, 8, 16)):
+    def __init__(self, model: str = "8b", reps: int = 40, splits=(1, 2, 4, 8, 16, 32, 64)):
         import workloads
         from .layer import LinearGroup, StoredLinear, UniformLinear
         from . import tuner as T
@@ -483,7 +483,7 @@ def tune(args):
     print(f"model {args.model}")
     print("target   split cap  split (qkv,o,gu,d)   k_chunk (qkv,o,gu,d)   baseline us  tuned us  slowdown  frozen")
     for target in (0.025, 0.05, 0.1, 0.2, 0.5, 1.0, 2.0, 4.0):
-        r = T.tune(h.types, h.measure, target, ntb_max_limit=16, k_chunk_limit=128)
+        r = T.tune(h.types, h.measure, target, ntb_max_limit=64, k_chunk_limit=128)
         names = [t for t, _, _ in h.ORDER]
         print(f"{target * 100:6.1f}%  {r.ntb_max:9d}  {str(tuple(r.ntb[n] for n in names)):19s}  "
               f"{str(tuple(r.k_chunk[n] for n in names)):21s}  {r.baseline:11.1f}  {r.time:8.1f}  {r.slowdown * 100:7.1f}%  "
