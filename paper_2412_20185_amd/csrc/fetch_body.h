@@ -96,7 +96,7 @@ __device__ __forceinline__ Selection obtain_selection(const uint16_t* __restrict
     }
 }
 
-// What one lane loads of one row: its 8 columns, BITS bits each.
+// What one lane loads of one row: 8 columns (16 of 2-bit codes), BITS bits each; never less than 4 bytes.
 template <int BITS>
 struct RowPiece;
 template <>
@@ -113,12 +113,12 @@ struct RowPiece<4> {
 };
 template <>
 struct RowPiece<2> {
-    typedef uint16_t type;
+    typedef uint32_t type;
 };
 
 // acc[i] += value of column i of the piece * xs.
-template <int BITS>
-__device__ __forceinline__ void accumulate_piece(const typename RowPiece<BITS>::type& v, float xs, float (&acc)[8]) {
+template <int BITS, int CPL>
+__device__ __forceinline__ void accumulate_piece(const typename RowPiece<BITS>::type& v, float xs, float (&acc)[CPL]) {
     if constexpr (BITS == 16) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -132,33 +132,37 @@ __device__ __forceinline__ void accumulate_piece(const typename RowPiece<BITS>::
         for (int i = 0; i < 8; ++i)
             acc[i] = fmaf((float)((int)(w[i >> 2] << (24 - 8 * (i & 3))) >> 24), xs, acc[i]);
     } else {
-        const uint32_t w = v;  // 8 two's-complement fields of BITS bits
+        const uint32_t w = v;  // CPL two's-complement fields of BITS bits
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < CPL; ++i)
             acc[i] = fmaf((float)((int)(w << (32 - BITS * (i + 1))) >> (32 - BITS)), xs, acc[i]);
     }
 }
 
-// One workgroup = one column segment of 512 columns (8 columns per lane: a lane reads 128 x BITS / 16 =
-// 16, 8, 4 or 2 bytes of every row, a wavefront 1 KiB down to 128 bytes of contiguous row) x the rows of row
-// slice rs; wavefront w < row_waves of it takes a contiguous share of those rows and keeps 64 / BITS x 4
-// rows in flight per lane (4 KiB per wavefront in every format).  BITS = 16: fp16 rows.  BITS = 2, 4, 8:
-// integer residuals (Section 4.2: 4-bit symmetric with one scale per output column; 2- and 8-bit are the
-// variants of the paper's bit-width study, Table 2),  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
+// One workgroup = one column segment of 512 columns x the rows of row slice rs.  A lane reads 8 columns of a
+// row (16, 8 or 4 bytes for fp16, 8-bit and 4-bit rows: a wavefront 1 KiB down to 256 bytes of contiguous
+// row) or 16 columns of a 2-bit row (4 bytes; the two halves of a wavefront then take different rows).
+// Wavefront w < row_waves takes a contiguous share of the workgroup's rows and keeps 4 KiB of row loads in
+// flight in every format.  BITS = 16: fp16 rows.  BITS = 2, 4, 8: integer residuals (Section 4.2: 4-bit
+// symmetric with one scale per output column; 2- and 8-bit are the variants of the paper's bit-width study,
+// Table 2),  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
 //
-// After the row loop the wavefronts' sums are added through LDS in the fixed order w = 0, 1, ...: thread
-// t of the workgroup ends up with the segment's sum for column t.  It writes it to row rs of cpart; with
-// in-kernel accumulation wavefront w then counts the workgroup in on the w-th 64-column tile of the
-// segment and adds that tile up if this completed it (finalize.h).
+// After the row loop the sums of the wavefronts (and half-wavefronts) are added through LDS in a fixed
+// order: thread t of the workgroup ends up with the segment's sum for column t.  It writes it to row rs of
+// cpart; with in-kernel accumulation wavefront w then counts the workgroup in on the w-th 64-column tile
+// of the segment and adds that tile up if this completed it (finalize.h).
 template <int BITS, int SELECT_NCH>
 __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const FinalizeArgs& fa,
                                             const uint16_t* __restrict__ x, int32_t* idx_g, uint16_t* xsel_g, int k,
                                             int K, int Ntot, float* __restrict__ cpart, int segments, int slices,
                                             int row_waves, int bid) {
     typedef typename RowPiece<BITS>::type piece_t;
-    constexpr int UNROLL = kUnroll * 16 / BITS;  // row loads in flight per lane
+    constexpr int CPL = BITS == 2 ? 16 : 8;             // columns per lane
+    constexpr int LPR = kFetchSegmentCols / CPL;        // lanes that cover the segment's part of one row
+    constexpr int SUB = 64 / LPR;                       // rows a wavefront loads with one instruction
+    constexpr int UNROLL = (4096 / 64) / (int)sizeof(piece_t);  // loads in flight per lane: 4 KiB per wavefront
     static_assert(kBlockThreads == kFetchSegmentCols, "one thread per column of the segment");
-    __shared__ float red[kWavesPerBlock][kBlockThreads];
+    __shared__ float red[kWavesPerBlock * SUB][kFetchSegmentCols];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -169,9 +173,10 @@ __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const Finaliz
     const BlockTask t = block_task(jobs, segments, bid);
     const int N = jobs.N[t.m];
     const piece_t* __restrict__ R = reinterpret_cast<const piece_t*>(jobs.R[t.m]);
-    const int piece = t.wc * 64 + lane;  // this lane's 8 columns of a row
-    const bool active = piece * 8 < N;
-    const size_t row_pieces = (size_t)(N / 8);
+    const int sub = lane / LPR;                       // which of the SUB rows of a load instruction
+    const int piece = t.wc * LPR + (lane % LPR);      // this lane's CPL columns of a row
+    const bool active = piece * CPL < N;
+    const size_t row_pieces = (size_t)(N / CPL);
     // rows of this wavefront: slice (rs, wave) out of slices * row_waves equal shares of the k selected rows
     const int rows_per = (k + slices * row_waves - 1) / (slices * row_waves);
     const int j0 = min((t.rs * row_waves + wave) * rows_per, k);
@@ -186,43 +191,45 @@ __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const Finaliz
         if (owns) sraw = jobs.Rs[t.m][ocol];
     }
 
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int j = j0; j < j1; j += UNROLL) {
+    float acc[CPL];
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) acc[i] = 0.f;
+    for (int j = j0; j < j1; j += UNROLL * SUB) {
         piece_t v[UNROLL];
         float xs[UNROLL];
         int row[UNROLL];
         uint32_t xraw[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {  // indices and activations first, so that no row load waits for them
-            const int jj = min(j + u, j1 - 1);
+            const int jj = min(j + u * SUB + sub, j1 - 1);
             row[u] = idx[jj];
             xraw[u] = xsel[jj];
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             v[u] = piece_t{};
-            if (j + u < j1 && active && (unsigned)row[u] < (unsigned)K) v[u] = R[(size_t)row[u] * row_pieces + piece];
+            if (j + u * SUB + sub < j1 && active && (unsigned)row[u] < (unsigned)K)
+                v[u] = R[(size_t)row[u] * row_pieces + piece];
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
-            xs[u] = (j + u < j1 && (unsigned)row[u] < (unsigned)K) ? h2f(xraw[u]) : 0.f;
+            xs[u] = (j + u * SUB + sub < j1 && (unsigned)row[u] < (unsigned)K) ? h2f(xraw[u]) : 0.f;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            if (j + u < j1) accumulate_piece<BITS>(v[u], xs[u], acc);  // wave-uniform: rows it does not have cost nothing
-        }
+        for (int u = 0; u < UNROLL; ++u)
+            if (j + u * SUB < j1) accumulate_piece<BITS, CPL>(v[u], xs[u], acc);  // wave-uniform: rows it does not have cost nothing
     }
 
-    // Sum over the wavefronts of the workgroup.
+    // Sum over the wavefronts (and their halves) of the workgroup.
     if (wave < row_waves) {
-        float4* dst = reinterpret_cast<float4*>(&red[wave][lane * 8]);
-        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        float4* dst = reinterpret_cast<float4*>(&red[wave * SUB + sub][(lane % LPR) * CPL]);
+#pragma unroll
+        for (int i = 0; i < CPL / 4; ++i) dst[i] = make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
     }
     __syncthreads();
     float val = red[0][tid];
 #pragma unroll
-    for (int w = 1; w < kWavesPerBlock; ++w)
-        if (w < row_waves) val += red[w][tid];  // wave-uniform
+    for (int w = 1; w < kWavesPerBlock * SUB; ++w)
+        if (w < row_waves * SUB) val += red[w][tid];  // wave-uniform
     if constexpr (BITS != 16) val *= h2f(sraw);
 
     const bool coherent = fa.counters != nullptr;

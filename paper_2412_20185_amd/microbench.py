@@ -3,6 +3,7 @@
     python -m paper_2412_20185_amd.microbench gemv     base GEMV kernel per shape: us, GB/s, fraction of 8 TB/s
     python -m paper_2412_20185_amd.microbench gemvshape  base GEMV launch shapes (waves per workgroup x groups per wave)
                                                        and the three ways of adding its partial rows
+    python -m paper_2412_20185_amd.microbench selcost  cost of the exact selection: its own kernel, and inside the one-grid kernel
     python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and row split: us, GB/s
     python -m paper_2412_20185_amd.microbench ksweep   latency of a Llama-3-8B layer versus k (4-bit weights),
                                                        next to the knee model of the paper (Section 5.1)
@@ -143,6 +144,46 @@ def gemvshape(args):
                 print(f"{model:4s} {name:8s} {tag:5s} {wpb:5d} {gpw:4d} {slices:6d} {how:>7s} {us:8.2f} {acc:7.2f} "
                       f"{call_us:8.2f} {nbytes / us / 1e3:10.0f} {nbytes / call_us / 1e3:10.0f}", flush=True)
             del Wq
+    ws.close()
+
+
+def selcost(args):
+    """What the exact selection costs where it runs: (a) the stand-alone selection kernel's duration, (b) the
+    one-grid compensated kernel selecting for itself against the same kernel with the selection supplied
+    (decdec_gemv_idx: its fetch workgroups read sc_indices from GPU memory instead of selecting).  3-bit
+    weights, fp16 host residuals, N = 4096, activations N(0,1) with 0.5 % outlier channels."""
+    import workloads
+    from .layer import StoredLinear
+    ws = B.Workspace(28672, 4096, 1024)
+    print(f"{'K':>6s} {'k':>5s} {'select kernel us':>17s} {'fused, selects us':>18s} {'fused, supplied us':>19s} {'difference us':>14s}")
+    for K in (4096, 8192, 14336, 28672):
+        lin = StoredLinear.random(K, 4096, 3, B.W_UNIFORM_G128, 16, seed=K)
+        xs = [torch.from_numpy(workloads.x_gauss_outliers(2, 0, 0, s, K)).cuda() for s in range(8)]
+        y = torch.empty(4096, dtype=torch.float16, device="cuda")
+        for frac in (0.001, 0.02):
+            k = workloads.k_for_fraction(K, frac)
+            idx = torch.empty(k, dtype=torch.int32, device="cuda")
+            xsel = torch.empty(k, dtype=torch.float16, device="cuda")
+            B.decdec_select_topk(xs[0], K, k, idx, xsel)
+            res = {}
+            for tag in ("select", "fused_selects", "fused_supplied"):
+                ws.set_mode(B.MODE_SERIAL if tag == "select" else B.MODE_FUSED)
+                ws.set_separate_select(tag == "select")
+                run = ((lambda i: B.decdec_gemv_idx(lin.desc, xs[0], lin.Wq, lin.scales, lin.zeros, lin.R, None, k, idx, xsel, y, ws))
+                       if tag == "fused_supplied" else (lambda i: lin.gemv(xs[i % 8], k, y, ws)))
+                for i in range(4):
+                    run(i)
+                torch.cuda.synchronize()
+                ws.set_profiling(args.reps)
+                for i in range(args.reps):
+                    run(i)
+                prof = ws.read_profile()
+                ws.set_profiling(0)
+                ms, n = prof["select" if tag == "select" else "fetch"]
+                res[tag] = ms * 1e3 / max(n, 1)
+            print(f"{K:6d} {k:5d} {res['select']:17.2f} {res['fused_selects']:18.2f} {res['fused_supplied']:19.2f} "
+                  f"{res['fused_selects'] - res['fused_supplied']:14.2f}", flush=True)
+        del lin
     ws.close()
 
 
@@ -494,7 +535,7 @@ def tune(args):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=("gemv", "gemvshape", "fetch", "ksweep", "select", "rformats", "configs", "tune"))
+    ap.add_argument("what", choices=("gemv", "gemvshape", "selcost", "fetch", "ksweep", "select", "rformats", "configs", "tune"))
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=12)
@@ -507,7 +548,7 @@ def main():
         print("needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    {"gemv": gemv, "gemvshape": gemvshape, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "configs": configs, "tune": tune}[args.what](args)
+    {"gemv": gemv, "gemvshape": gemvshape, "selcost": selcost, "fetch": fetch, "ksweep": ksweep, "select": select, "rformats": rformats, "configs": configs, "tune": tune}[args.what](args)
     return 0
 
 
