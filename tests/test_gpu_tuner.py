@@ -1,6 +1,6 @@
 """The parameter tuner of Section 4.4 driven by real measurements on the GPU: one Llama-3-8B-shaped
 layer (3-bit weights, fp16 host residuals), measure() = wall time of the layer's four calls replayed
-as a captured graph, target slowdown 10 % over the uncompensated layer."""
+as a captured graph, target slowdowns of 10 % and 30 % over the uncompensated layer."""
 import pytest
 
 from paper_2412_20185_amd import tuner as T
@@ -10,8 +10,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(600)
-def test_tuned_configuration_meets_the_target_and_is_maximal():
-    target = 0.10
+@pytest.mark.parametrize("target", [0.10, 0.30])
+def test_tuned_configuration_meets_the_target_and_is_maximal(target):
     h = LayerHarness("8b", reps=30)
     try:
         r = T.tune(h.types, h.measure, target, ntb_max_limit=64, k_chunk_limit=128)
@@ -37,8 +37,10 @@ def test_tuned_configuration_meets_the_target_and_is_maximal():
         tuned_again = h.time_once(cfg)
         assert abs(base_again / r.baseline - 1.0) < 0.05, (base_again, r.baseline)
         assert tuned_again / base_again - 1.0 <= target + 0.03, (tuned_again, base_again)
-        # the machine's knee (Section 5.1) is below one channel per 1024 for fp16 residuals, so a 10 % budget
-        # buys only a few channels
+        # the machine's knee (Section 5.1) is below one channel per 1024 for fp16 residuals, so budgets like
+        # these buy only a few channels (none at all where one channel already costs more than the budget)
         assert max(r.k_chunk.values()) <= 8
+        if target >= 0.30:
+            assert max(r.k_chunk.values()) >= 1
     finally:
         h.close()
