@@ -3,9 +3,12 @@
 // The paper adds o_dec into o_b with atomics from inside its fused kernel
 // (Section 4.3 "Kernel Fusion").  Here both producers leave fp32 partial rows
 // (the base GEMV one per K-slice, the residual kernel one per slice of the
-// selected channels) and this kernel, enqueued on the caller's stream after
-// both, adds them in a fixed order and rounds once to fp16: the result does
-// not depend on which kernel finished first.
+// selected channels), which are added in a fixed order and rounded once to
+// fp16, so that the result does not depend on which producer finished first.
+// By default the producers do that themselves (finalize.h: the last workgroup
+// of a 64-column tile adds the tile); this kernel is the other way to do it
+// (decdec_ws_set_inkernel_accumulate(ws, 0)): enqueued on the caller's stream
+// after both producers, same order, same bits.
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"

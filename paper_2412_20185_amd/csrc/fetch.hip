@@ -75,7 +75,7 @@ static hipError_t launch_fetch_nch(int rfmt, const FetchJobs& jobs, const Finali
 hipError_t launch_fetch(int rfmt, const MultiShape& sh, const FetchOperands& op, const void* x, int select_chunks,
                         int32_t* idx, void* xsel, int k, float* cpart, const FetchPlan& plan, const FinalizeArgs& fa,
                         hipStream_t stream, const KernelTimer* tm) {
-    const FetchJobs jobs = make_fetch_jobs(rfmt, sh, op);
+    const FetchJobs jobs = make_fetch_jobs(sh, op);
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* xs = static_cast<uint16_t*>(xsel);
     const int Ntot = sh.col0[sh.n];

@@ -240,7 +240,7 @@ __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const Finaliz
 }
 
 // Host: kernel-side description of the matrices of one call.
-inline FetchJobs make_fetch_jobs(int rfmt, const MultiShape& sh, const FetchOperands& op) {
+inline FetchJobs make_fetch_jobs(const MultiShape& sh, const FetchOperands& op) {
     FetchJobs jobs{};
     jobs.n = sh.n;
     const int cpw = kFetchSegmentCols;

@@ -14,7 +14,8 @@
 // partial rows up (finalize.h), so nothing has to be joined and nothing else
 // has to be launched.  (fp16 and 4-bit residuals; the 2- and 8-bit variants
 // of the bit-width study use the separate kernels.)  How many workgroups fetch (the paper's n_tb,
-// Section 4.4) is the row split of the residual kernel.
+// Section 4.4) follows from the number of wavefronts that share the rows of a
+// column segment (decdec_ws_set_fetch_split).
 #include <hip/hip_runtime.h>
 
 #include "fetch_body.h"
@@ -78,7 +79,7 @@ hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, con
     if (rfmt != 0 && rfmt != 1) return hipErrorInvalidValue;  // built for fp16 and 4-bit residuals only
     const int G = sh.K / kGroup;
     GemvJobs gj{};
-    const FetchJobs fj = make_fetch_jobs(rfmt, sh, fop);
+    const FetchJobs fj = make_fetch_jobs(sh, fop);
     gj.n = sh.n;
     int tiles = 0;
     for (int m = 0; m < sh.n; ++m) {

@@ -20,9 +20,11 @@
 //   * the zero point is factored out of the inner loop:
 //     sum_k s (q_k - z) x_k = s (sum_k q_k x_k - z sum_k x_k), with the
 //     group's sum of x formed once per wave by a DPP reduction;
-//   * K is split over the waves of a workgroup and over workgroups; a
-//     workgroup reduces its waves through LDS and writes one fp32 partial row,
-//     the accumulate kernel (accumulate.hip) adds the partial rows.
+//   * K is split over the waves of a workgroup and, where one workgroup per
+//     64-column tile would leave compute units idle, over workgroups; a
+//     workgroup reduces its waves through LDS and either writes y itself (one
+//     K-slice, no residual term) or writes one fp32 partial row and counts
+//     itself in on the tile (finalize.h).
 #pragma once
 #include <hip/hip_runtime.h>
 

@@ -4,7 +4,7 @@
     python -m paper_2412_20185_amd.microbench gemvshape  base GEMV launch shapes (waves per workgroup x groups per wave)
                                                        and the three ways of adding its partial rows
     python -m paper_2412_20185_amd.microbench selcost  cost of the exact selection: its own kernel, and inside the one-grid kernel
-    python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and row split: us, GB/s
+    python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and number of wavefronts per column segment: us, GB/s
     python -m paper_2412_20185_amd.microbench ksweep   latency of a Llama-3-8B layer versus k (4-bit weights),
                                                        next to the knee model of the paper (Section 5.1)
     python -m paper_2412_20185_amd.microbench select   exact radix select versus the paper's approximate bucket
@@ -193,7 +193,7 @@ def fetch(args):
     ws.set_separate_select(True)
     cases = [(4096, 1024, 81), (4096, 4096, 81), (4096, 6144, 81), (4096, 14336, 81), (14336, 4096, 286),
              (4096, 28672, 81), (4096, 4096, 512), (8192, 28672, 81), (28672, 8192, 286)]
-    print("residual fetch kernel (fp16 rows, zero-copy): us / GB/s per row split (0 = built-in choice)")
+    print("residual fetch kernel (fp16 rows, zero-copy): us / GB/s per number of wavefronts that share a column segment (0 = built-in choice)")
     for K, N, k in cases:
         d, Wq, sc, zl, _ = _operands(K, N, 3, B.W_UNIFORM_G128, copies_bytes=0)
         R = torch.empty((K, N), dtype=torch.float16, pin_memory=True)

@@ -249,7 +249,7 @@ def test_in_kernel_accumulate_equals_separate_kernel_bitwise(ws):
                 assert torch.equal(y.view(torch.int16), want[rep % len(xs)].view(torch.int16)), (k, rep)
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), want[59 % len(xs)].view(torch.int16))
-    ws.set_inkernel_accumulate(False)
+    ws.set_inkernel_accumulate(True)          # the default, for the tests that follow on this workspace
 
 
 @pytest.mark.parametrize("K,N,k", [(4096, 1024, 81), (8192, 512, 300), (14336, 1024, 286), (16384, 256, 4096),
