@@ -107,21 +107,19 @@ typedef struct decdec_ws decdec_ws; /* opaque workspace */
 /* Allocates everything the hot path needs for problems up to (maxK, maxN)
  * with up to maxk salient channels: a side stream and two events for the
  * overlap of Section 4.1, the sc_indices / x[sc_indices] buffer of
- * maxk*(4+2) bytes (Section 4.3 "GPU Memory Overhead"), and fp32 partial
- * output buffers.  One workspace can be reused for every layer. */
+ * maxk*(4+2) bytes (Section 4.3 "GPU Memory Overhead"), and one 64-bit
+ * accumulator per output column (8 maxN bytes) into which the base GEMV and
+ * the residual kernel add.  One workspace can be reused for every layer. */
 int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out);
 int decdec_ws_destroy(decdec_ws* ws);
 /* Size in bytes of the sc_indices + x[sc_indices] buffer for k channels: the
  * only extra GPU memory of the paper's kernel (Section 4.3: 1433 channels ->
  * 8.6 KB). */
 size_t decdec_sc_buffer_bytes(int32_t k);
-/* Size in bytes of the fp32 partial rows a workspace for maxN output columns
- * holds in addition: the base GEMV splits K over workgroups and the residual
- * kernel splits the selected rows, each leaves up to 16 partial rows of maxN
- * floats, and a fixed-order sum of those rows replaces the paper's atomic adds
- * into o_b.  That is 128 maxN bytes (3.7 MB for the 28672 columns of gate + up
- * of Llama-3-8B): extra GPU memory the paper's design does not need, the price
- * of a result that does not depend on the order of floating-point atomics. */
+/* Size in bytes of the fp32 partial rows that a workspace for maxN output
+ * columns allocates when decdec_ws_set_inkernel_accumulate(ws, 0) is first
+ * called (up to 16 rows of maxN floats from each of the two producers, 128 maxN
+ * bytes); a workspace that keeps the default never holds them. */
 size_t decdec_partial_buffer_bytes(int32_t maxN);
 /* Device pointers to the selection of the most recent decdec_gemv call on
  * this workspace (valid once that call's work has run). */
@@ -135,14 +133,14 @@ int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, 
  * in the residual kernel, 1 .. 128 (the counterpart of n_tb in Section 4.4:
  * how many requests are in flight on the host link, at the price of compute
  * units the base GEMV cannot use); they are grouped into workgroups of 8, each
- * of which leaves one fp32 partial row.  0 restores the built-in choice (about
+ * of which adds its rows' sum once per column.  0 restores the built-in choice (about
  * 128 wavefronts in the whole kernel, which saturate the link; more than about
  * 500 lower its rate).  Affects later calls on this workspace. */
 int decdec_ws_set_fetch_split(decdec_ws* ws, int32_t row_split);
 
 /* How one compensated GEMV (k > 0) is laid out on the GPU.  Every mode adds the
- * same terms in fp32; SERIAL and TWO_STREAMS give identical bits, FUSED splits K
- * over larger workgroups, so its partial sums may round differently.
+ * same terms in fp32; SERIAL and TWO_STREAMS give identical bits, FUSED may split
+ * K over workgroups of another size, so its part sums may round differently.
  *   FUSED (default): one kernel whose first workgroups do steps 1-3 (selection,
  *     zero-copy fetch, residual GEMV) and whose other workgroups do the base
  *     GEMV, on the caller's stream (fp16 and 4-bit residuals; the 2- and 8-bit
@@ -163,13 +161,23 @@ int decdec_ws_set_mode(decdec_ws* ws, int32_t mode);
  * selection is the same either way. */
 int decdec_ws_set_separate_select(decdec_ws* ws, int32_t on);
 
-/* How the partial results of the base GEMV and of the residual kernel are
- * added (step 4 of Section 4.1; the paper adds with atomics from its fused
- * kernel).  on = 1 (default): whichever workgroup of either producer completes
- * a 64-column tile of the output last adds the tile's partial rows in a fixed
- * order and writes y: no further launch, and the sum does not depend on who
- * came last.  on = 0: a small kernel of its own on the caller's stream, after
- * both producers, adds them in the same order (same bits). */
+/* How the part sums of the base GEMV (one per K-slice) and of the residual
+ * kernel (one per slice of the selected channels) are added (step 4 of Section
+ * 4.1; the paper adds with atomics from its fused kernel).
+ *   on = 1 (default): with atomics, as in the paper, but in fixed point, so
+ *     that the result does not depend on the order of arrival: every producer
+ *     converts its fp32 part sum of a column to a multiple of 2^-30 and adds it
+ *     to the column's 64-bit accumulator with one atomic, which also counts the
+ *     producers; the one that arrives last rounds the sum to fp16, writes y and
+ *     clears the accumulator.  No further launch.
+ *   on = 0: the producers write fp32 partial rows and a small kernel of its own
+ *     on the caller's stream, after both, converts and adds them the same way
+ *     (same bits).  The first such call allocates the partial rows
+ *     (decdec_partial_buffer_bytes; DECDEC_ENOMEM if that fails).
+ * Range: a part sum is clamped to +-2^21 before conversion, 32 times beyond
+ * what fp16 can hold: a clamped term leaves y infinite, as it would be without
+ * the clamp, unless clamped terms of both signs meet in one column.  Inputs
+ * are assumed finite; a NaN part sum counts as -2^21. */
 int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on);
 
 /* Number of 128-channel groups each wavefront of the base GEMV walks through
@@ -287,7 +295,7 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  * queries, no stream work, so this too is legal during capture); every later
  * call finds it in the workspace's table (decdec_ws_forget_pointer).  Calls
  * that share a workspace must be ordered on one stream: they share its
- * partial-row and selection buffers.
+ * accumulators and selection buffer.
  * Errors: DECDEC_EINVAL for null / misaligned / out-of-range arguments and for
  * a residual allocation shorter than K rows, DECDEC_EUNSUPPORTED
  * for a format combination that is not built, DECDEC_ENOTPINNED if R_pinned
@@ -330,8 +338,8 @@ int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x
 /* decdec_gemv for callers that cannot allocate: code running under HIP graph
  * capture before any workspace exists, tight serving loops, harnesses that
  * forbid hipMalloc.  Same computation and same kernels as decdec_gemv in its
- * default mode, but no workspace: the selection buffer and the fp32 partial
- * rows live in a fixed array in the library's device image (about 2.1 MB, held
+ * default mode, but no workspace: the selection buffer and the per-column
+ * accumulators live in a fixed array in the library's device image (280 KB, held
  * by every GPU the library runs on until the process ends).  The call
  * allocates nothing, on the host or on the device.
  *   Limits: N <= DECDEC_STATIC_MAX_N, k <= DECDEC_STATIC_MAX_SELECTED;
@@ -340,8 +348,8 @@ int decdec_gemv_multi(int32_t count, const decdec_linear* linears, const void* x
  * All calls on one GPU share that GPU's array: calls that overlap in time on
  * one GPU (different streams without ordering between them) race.  The first
  * call on a GPU looks the array's address up; make it outside graph capture. */
-#define DECDEC_STATIC_MAX_N 16384
-#define DECDEC_STATIC_MAX_SELECTED 2048
+#define DECDEC_STATIC_MAX_N 32768
+#define DECDEC_STATIC_MAX_SELECTED 4096
 int decdec_gemv_static(const decdec_desc* d, const void* x_f16_dev, const void* Wq_dev,
                        const void* scales_f16_dev, const void* zeros_or_lut_f16_dev,
                        const void* R_pinned, const void* R_scales_f16_dev,

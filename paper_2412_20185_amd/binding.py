@@ -146,7 +146,7 @@ def decdec_partial_buffer_bytes(maxN: int) -> int:
     return int(lib().decdec_partial_buffer_bytes(maxN))
 
 
-STATIC_MAX_N, STATIC_MAX_SELECTED = 16384, 2048
+STATIC_MAX_N, STATIC_MAX_SELECTED = 32768, 4096
 
 
 def decdec_check_pinned(t) -> int:

@@ -126,13 +126,13 @@ struct Core {
     int32_t gemv_wpb;             // wavefronts per base-GEMV workgroup when it runs as a kernel of its own; 0: built in
     int32_t mode;                 // decdec_mode
     int32_t separate_select;      // 1: selection always runs as a kernel of its own
-    int32_t inkernel_accumulate;  // 1: the last producer of a tile adds the partial rows (no accumulate kernel)
-    int32_t counters_dirty;       // a call failed half-way: clear the counters before the next one
+    int32_t inkernel_accumulate;  // 1: the producers add into the column accumulators (no accumulate kernel)
+    int32_t acc_dirty;            // a call failed half-way: clear the accumulators before the next one
     int32_t* idx;        // [maxk]
     void* xsel;          // fp16 [maxk]
-    float* gpart;        // [kMaxGemvSlices][maxN]
-    float* cpart;        // [kMaxFetchSlices][maxN]
-    unsigned* counters;  // [maxN/64 + 1] per-tile arrival counters, zero between calls
+    unsigned long long* acc;  // [maxN] per-column fixed-point accumulators, zero between calls
+    float* gpart;        // [kMaxGemvSlices][maxN]   partial rows for the separate accumulate kernel:
+    float* cpart;        // [kMaxFetchSlices][maxN]  allocated when that path is first switched on
     hipStream_t side;    // null: no second stream (TWO_STREAMS mode unavailable)
     hipEvent_t ev_fork, ev_join;
     PointerTable ptrs;
@@ -214,10 +214,8 @@ int decdec_ws_create(int32_t maxK, int32_t maxN, int32_t maxk, decdec_ws** out) 
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c.ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.idx), kk * 4);
     if (e == hipSuccess) e = hipMalloc(&c.xsel, kk * 2);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.gpart), (size_t)kMaxGemvSlices * maxN * 4);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.cpart), (size_t)kMaxFetchSlices * maxN * 4);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.counters), ((size_t)maxN / 64 + 1) * 4);
-    if (e == hipSuccess) e = hipMemset(c.counters, 0, ((size_t)maxN / 64 + 1) * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.acc), (size_t)maxN * 8);
+    if (e == hipSuccess) e = hipMemset(c.acc, 0, (size_t)maxN * 8);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         const int rc = e == hipErrorOutOfMemory ? DECDEC_ENOMEM : hip_fail(e);
@@ -326,7 +324,7 @@ int decdec_ws_destroy(decdec_ws* ws) {
     if (c.xsel) (void)hipFree(c.xsel);
     if (c.gpart) (void)hipFree(c.gpart);
     if (c.cpart) (void)hipFree(c.cpart);
-    if (c.counters) (void)hipFree(c.counters);
+    if (c.acc) (void)hipFree(c.acc);
     delete ws;
     return DECDEC_OK;
 }
@@ -340,7 +338,20 @@ int decdec_ws_last_selection(const decdec_ws* ws, const int32_t** idx_dev, const
 
 int decdec_ws_set_inkernel_accumulate(decdec_ws* ws, int32_t on) {
     if (ws == nullptr || (on != 0 && on != 1)) return DECDEC_EINVAL;
-    ws->core.inkernel_accumulate = on;
+    Core& c = ws->core;
+    if (on == 0 && c.gpart == nullptr) {
+        // The separate kernel adds fp32 partial rows; they exist only for workspaces that ask for it.
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&c.gpart), (size_t)kMaxGemvSlices * c.maxN * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c.cpart), (size_t)kMaxFetchSlices * c.maxN * 4);
+        if (e != hipSuccess) {
+            const int rc = e == hipErrorOutOfMemory ? DECDEC_ENOMEM : hip_fail(e);
+            (void)hipGetLastError();
+            if (c.gpart) (void)hipFree(c.gpart);
+            c.gpart = c.cpart = nullptr;
+            return rc;
+        }
+    }
+    c.inkernel_accumulate = on;
     return DECDEC_OK;
 }
 
@@ -617,8 +628,8 @@ int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t 
         ++c.prof_used;
     }
 
-    // Split of the work, known up front because each kernel must know how many
-    // partial rows the other one contributes.
+    // Split of the work, known up front because every producer must know how many
+    // producers a column has in all.
     long tiles = 0;
     for (int m = 0; m < count; ++m) tiles += sh.N[m] / kTileCols;
     // The one-grid kernel is built for fp16 and 4-bit residuals; the other formats take the separate kernels.
@@ -631,25 +642,22 @@ int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t 
     const int cslices = plan.slices;
 
     FinalizeArgs fa{};
-    int t0 = 0;
     for (int m = 0; m < count; ++m) {
         fa.y[m] = static_cast<_Float16*>(ys[m]);
         fa.col0[m] = sh.col0[m];
-        fa.tile0[m] = t0;
-        t0 += sh.N[m] / kTileCols;
     }
+    fa.acc = c.inkernel_accumulate ? c.acc : nullptr;
     fa.gpart = c.gpart;
     fa.cpart = c.cpart;
     fa.gslices = gslices;
     fa.cslices = cslices;
     fa.Ntot = sh.col0[count];
-    fa.counters = c.inkernel_accumulate ? c.counters : nullptr;
     // One slice and no residual term: the base GEMV rounds and writes y itself, nothing is left to add.
     fa.direct = k == 0 && gslices == 1 ? 1 : 0;
 
-    if (c.counters_dirty) {
-        DD_HIP(launch_clear_u32(c.counters, c.maxN / 64 + 1, stream));
-        c.counters_dirty = 0;
+    if (c.acc_dirty) {
+        DD_HIP(launch_clear_u32(reinterpret_cast<unsigned*>(c.acc), 2 * c.maxN, stream));
+        c.acc_dirty = 0;
     }
     bool forked = false;  // TWO_STREAMS: the side stream has been made to wait for `stream` and not yet joined back
     const int rc_enq = [&]() -> int {
@@ -702,7 +710,7 @@ int gemv_common(int32_t count, const decdec_linear* lin, const void* x, int32_t 
         return DECDEC_OK;
     }();
     if (rc_enq != DECDEC_OK) {
-        c.counters_dirty = 1;  // some producers may never arrive
+        c.acc_dirty = 1;  // some producers may never arrive
         if (forked) {
             // Join the side stream back so that `stream` (and a capture in progress) is left whole.
             if (hipEventRecord(c.ev_join, c.side) == hipSuccess) (void)hipStreamWaitEvent(stream, c.ev_join, 0);
@@ -762,10 +770,8 @@ namespace {
 constexpr size_t round256(size_t n) { return (n + 255) / 256 * 256; }
 constexpr size_t kStIdxOff = 0;
 constexpr size_t kStXselOff = kStIdxOff + round256((size_t)DECDEC_STATIC_MAX_SELECTED * 4);
-constexpr size_t kStCountersOff = kStXselOff + round256((size_t)DECDEC_STATIC_MAX_SELECTED * 2);
-constexpr size_t kStGpartOff = kStCountersOff + round256(((size_t)DECDEC_STATIC_MAX_N / 64 + 1) * 4);
-constexpr size_t kStCpartOff = kStGpartOff + (size_t)kMaxGemvSlices * DECDEC_STATIC_MAX_N * 4;
-constexpr size_t kStaticScratchBytes = kStCpartOff + (size_t)kMaxFetchSlices * DECDEC_STATIC_MAX_N * 4;
+constexpr size_t kStAccOff = kStXselOff + round256((size_t)DECDEC_STATIC_MAX_SELECTED * 2);
+constexpr size_t kStaticScratchBytes = kStAccOff + (size_t)DECDEC_STATIC_MAX_N * 8;
 
 constexpr int kMaxDevices = 16;
 struct StaticState {
@@ -778,8 +784,8 @@ std::mutex g_static_mutex;
 
 }  // namespace
 
-// Scratch memory of decdec_gemv_static: the selection buffer, the per-tile counters and the fp32 partial rows
-// of both producers, for problems up to DECDEC_STATIC_MAX_N columns and DECDEC_STATIC_MAX_SELECTED channels.
+// Scratch memory of decdec_gemv_static: the selection buffer and the per-column accumulators the producers
+// add into, for problems up to DECDEC_STATIC_MAX_N columns and DECDEC_STATIC_MAX_SELECTED channels.
 // Every GPU the library runs on holds its own copy at its own address until the process ends.  In host code
 // this name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
@@ -808,13 +814,11 @@ int decdec_gemv_static(const decdec_desc* d, const void* x_f16_dev, const void* 
         c.maxk = DECDEC_STATIC_MAX_SELECTED;
         c.idx = reinterpret_cast<int32_t*>(base + kStIdxOff);
         c.xsel = base + kStXselOff;
-        c.counters = reinterpret_cast<unsigned*>(base + kStCountersOff);
-        c.gpart = reinterpret_cast<float*>(base + kStGpartOff);
-        c.cpart = reinterpret_cast<float*>(base + kStCpartOff);
+        c.acc = reinterpret_cast<unsigned long long*>(base + kStAccOff);
         c.ptrs.e = st.slots;
         c.ptrs.cap = kStaticPointerSlots;
         c.inkernel_accumulate = 1;
-        c.counters_dirty = 1;  // the first call clears the counters with a fill kernel on its stream
+        c.acc_dirty = 1;  // the first call clears the accumulators with a fill kernel on its stream
         st.ready = true;
     }
     if (check_desc(d) == DECDEC_OK && (d->N > DECDEC_STATIC_MAX_N || k > DECDEC_STATIC_MAX_SELECTED))

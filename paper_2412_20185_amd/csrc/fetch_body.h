@@ -33,7 +33,6 @@
 
 namespace decdec {
 
-constexpr int kUnroll = 4;            // 16-byte row loads in flight per lane (narrower loads: as many more)
 constexpr int kFetchSegmentCols = 512;  // output columns of one column segment = threads of a workgroup
 
 __device__ __forceinline__ float h2f(uint32_t bits16) {
@@ -148,9 +147,8 @@ __device__ __forceinline__ void accumulate_piece(const typename RowPiece<BITS>::
 // Table 2),  o_dec[n] = S[n] * sum_j q[s_j][n] x[s_j].
 //
 // After the row loop the sums of the wavefronts (and half-wavefronts) are added through LDS in a fixed
-// order: thread t of the workgroup ends up with the segment's sum for column t.  It writes it to row rs of
-// cpart; with in-kernel accumulation wavefront w then counts the workgroup in on the w-th 64-column tile
-// of the segment and adds that tile up if this completed it (finalize.h).
+// order: thread t of the workgroup ends up with the segment's sum for column t and adds it into the
+// column's accumulator (finalize.h), or, when a separate kernel does the adding, writes it to row rs of cpart.
 template <int BITS, int SELECT_NCH>
 __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const FinalizeArgs& fa,
                                             const uint16_t* __restrict__ x, int32_t* idx_g, uint16_t* xsel_g, int k,
@@ -232,11 +230,13 @@ __device__ __forceinline__ void fetch_block(const FetchJobs& jobs, const Finaliz
         if (w < row_waves * SUB) val += red[w][tid];  // wave-uniform
     if constexpr (BITS != 16) val *= h2f(sraw);
 
-    const bool coherent = fa.counters != nullptr;
-    if (owns) store_partial(cpart + (size_t)t.rs * Ntot + jobs.col0[t.m] + ocol, val, coherent);
-    // In-kernel accumulation: wavefront w holds exactly the 64 columns of tile w of the segment.
-    const int tile = t.wc * (kFetchSegmentCols / 64) + wave;
-    if (coherent && tile * 64 < N) wave_arrive_and_finalize(fa, t.m, tile, lane);
+    if (owns) {
+        if (fa.acc != nullptr) {
+            arrive(fa, t.m, ocol, val);
+        } else {
+            cpart[(size_t)t.rs * Ntot + jobs.col0[t.m] + ocol] = val;
+        }
+    }
 }
 
 // Host: kernel-side description of the matrices of one call.

@@ -38,26 +38,16 @@ hipError_t launch_waves(int wpb, int nbuf, const KernelTimer* tm, dim3 grid, hip
 }  // namespace
 
 GemvPlan gemv_plan(long tiles, int G, int gpw_request, int wpb_request) {
-    // One or two groups per wavefront, so that a wavefront requests all its weights at once, as long as
-    // the chip holds the wavefronts that makes (256 compute units x 32); then the largest workgroups, which
-    // keep the K-slices few: every slice beyond the first is one more partial row to write, to wait for
-    // and to add, and a workgroup that walks all of K writes y itself.  Matrices beyond that run in several
-    // rounds of workgroups, which smaller workgroups fill more evenly.
+    // One group per wavefront, so that a wavefront requests all its weights at once, as long as the chip
+    // holds the wavefronts that makes at one time; two groups beyond that.  A K-slice more costs one atomic
+    // per column (finalize.h), so the slices are not kept few: small matrices take small workgroups, which
+    // start sooner and spread over more compute units; in between, the largest workgroups (a workgroup that
+    // walks all of K alone writes y itself); the largest matrices run in several rounds of workgroups,
+    // which medium workgroups fill more evenly.  Read from a sweep over the shapes of Llama-3 8B and 70B.
     GemvPlan p;
     const long units = tiles * G;  // (tile, group) pairs = wavefront iterations
-    p.wpb = wpb_request > 0 ? wpb_request : units <= 16384 ? 16 : 8;
-    if (gpw_request > 0) {
-        p.gpw = gpw_request;
-    } else if (units <= 12288) {
-        p.gpw = 1;
-    } else if (units <= 16384) {
-        p.gpw = 2;
-    } else {
-        p.gpw = (G + 4 * p.wpb - 1) / (4 * p.wpb);  // at most four K-slices
-        if (p.gpw < 2) p.gpw = 2;
-    }
-    const int gpw_8_slices = (G + 8 * p.wpb - 1) / (8 * p.wpb);  // never more than eight partial rows by choice
-    if (gpw_request <= 0 && p.gpw < gpw_8_slices) p.gpw = gpw_8_slices;
+    p.wpb = wpb_request > 0 ? wpb_request : units <= 4096 ? 4 : units <= 16384 ? 16 : 8;
+    p.gpw = gpw_request > 0 ? gpw_request : units <= 12288 ? 1 : 2;
     int per_block = p.gpw * p.wpb;
     p.slices = (G + per_block - 1) / per_block;
     while (p.slices > kMaxGemvSlices) {

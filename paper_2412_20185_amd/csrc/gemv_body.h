@@ -23,8 +23,8 @@
 //   * K is split over the waves of a workgroup and, where one workgroup per
 //     64-column tile would leave compute units idle, over workgroups; a
 //     workgroup reduces its waves through LDS and either writes y itself (one
-//     K-slice, no residual term) or writes one fp32 partial row and counts
-//     itself in on the tile (finalize.h).
+//     K-slice, no residual term) or adds its sums into the per-column
+//     accumulators with one atomic per column (finalize.h).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -298,9 +298,10 @@ __device__ __forceinline__ void gemv_block(const GemvJobs& jobs, const FinalizeA
             for (int w = 0; w + span < WPB; w += 2 * span) v[w] += v[w + span];
         if (fa.direct) {
             fa.y[m][n] = (_Float16)v[0];
+        } else if (fa.acc != nullptr) {
+            arrive(fa, m, n, v[0]);
         } else {
-            store_partial(part + (size_t)ks * Ntot + jobs.col0[m] + n, v[0], fa.counters != nullptr);
-            if (fa.counters != nullptr) wave_arrive_and_finalize(fa, m, nt, lane);
+            part[(size_t)ks * Ntot + jobs.col0[m] + n] = v[0];
         }
     }
 }

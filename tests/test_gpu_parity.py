@@ -84,6 +84,66 @@ def test_all_integer_case_is_bit_exact(ws):
         assert np.array_equal(y.astype(np.float64), y_ref)
 
 
+def _integer_problem(codes, R):
+    K, N = codes.shape
+    p = Problem.__new__(Problem)
+    p.K, p.N, p.bits = K, N, 4
+    p.codes = codes
+    p.scales = np.ones((K // 128, N), np.float16)
+    p.zeros = np.zeros((K // 128, N), np.float16)
+    p.lut = None
+    p.R = R
+    p.R_real, p.Rq, p.Rs, p.rfmt = p.R, None, None, "fp16"
+    p.desc = dd.Desc(K, N, 4)
+    p.W_hat = oracle.dequantize_uniform(p.codes, p.scales, p.zeros)
+    p._dev = None
+    return p
+
+
+def test_large_part_sums_that_cancel_are_added_exactly(ws):
+    """The K-slices and the residual term are added in fixed point with a step of 2^-30 and a range of
+    +-2^21 per term.  Here the two halves of K give part sums near +-10^6 (inside that range) that cancel
+    down to small multiples of 128, and the residual term adds halves: y must equal the oracle bit for bit."""
+    g = np.random.default_rng(11)
+    K, N, k = 1024, 256, 16
+    half = g.integers(0, 16, size=(K // 2, N)).astype(np.uint8)
+    other = half.copy()
+    bump = (g.random(size=other.shape) < 0.002) & (other < 15)
+    other[bump] += 1
+    R = np.zeros((K, N), np.float16)
+    R[:k] = (g.integers(-1, 2, size=(k, N)) * 2.0 ** -8).astype(np.float16)          # 128 * 2^-8 = 0.5
+    p = _integer_problem(np.concatenate([half, other]), R)
+    x = np.concatenate([np.full(K // 2, 128.0), np.full(K // 2, -128.0)]).astype(np.float16)
+    y_ref, sc = p.reference(x, k)
+    assert np.array_equal(sc, np.arange(k))                     # all |x| equal: the lowest indices win
+    part = np.abs(p.W_hat[:K // 2].T @ x[:K // 2].astype(np.float64))
+    assert 4e5 < part.max() < 2.0 ** 21 and np.abs(y_ref).max() < 1024 and np.count_nonzero(y_ref % 1) > N // 4
+    y, idx, _ = p.run(x, k, ws)
+    assert np.array_equal(idx, sc)
+    assert np.array_equal(y.astype(np.float64), y_ref)
+
+
+def test_sums_beyond_fp16_range_are_infinite_as_in_the_oracle(ws):
+    """Part sums beyond +-2^21 are clamped before they are added; the result is then far outside fp16's
+    range on the same side, so y is the infinity the fp64 sum rounds to."""
+    g = np.random.default_rng(12)
+    K, N = 1024, 128
+    codes = g.integers(8, 16, size=(K, N)).astype(np.uint8)
+    p = _integer_problem(codes, np.zeros((K, N), np.float16))
+    x = np.full(K, 2048.0, np.float16)
+    x[K // 2:] = 4096.0
+    sign = np.where(np.arange(N) % 2 == 0, 1.0, -1.0)
+    p.scales = (np.ones((K // 128, N)) * sign).astype(np.float16)
+    p.W_hat = oracle.dequantize_uniform(p.codes, p.scales, p.zeros)
+    y_ref, sc = p.reference(x, 0)
+    assert np.abs(y_ref).min() > 2.0 ** 22
+    y, _, _ = p.run(x, 0, ws)
+    with np.errstate(over="ignore"):
+        y_ref16 = y_ref.astype(np.float16)
+    assert np.array_equal(y.astype(np.float64), y_ref16.astype(np.float64))
+    assert np.all(np.isinf(y)) and np.array_equal(np.sign(y.astype(np.float64)), sign)
+
+
 @pytest.mark.parametrize("K,N", [(1024, 1024), (512, 192), (2048, 320)])
 def test_lut3_shapes_and_k(ws, K, N):
     """Config 4 style: per-column 8-entry codebook, Student-t activations."""

@@ -58,6 +58,6 @@ def test_static_entry_point_rejects_sizes_beyond_its_scratch():
     P = 1 << 20
     too_wide = dd.Desc(128, dd.STATIC_MAX_N + 64, 3)
     assert L.decdec_gemv_static(C.byref(too_wide), P, P, P, P, P, None, 0, P, None) == -6
-    ok_shape = dd.Desc(4096, 4096, 3)
+    ok_shape = dd.Desc(8192, 4096, 3)
     assert L.decdec_gemv_static(C.byref(ok_shape), P, P, P, P, P, None, dd.STATIC_MAX_SELECTED + 1, P, None) == -6
     assert "static" in dd.decdec_strerror(-6)
