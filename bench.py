@@ -40,7 +40,7 @@ LINK_PEAK_GBS = 64.0        # PCIe Gen5 x16, one direction (the box reports 32 G
 LINK_MEASURED_GBS = 57.5    # what zero-copy reads and hipMemcpy both reach on the box
 K_FRACTION = 0.02
 CPU_STEPS = 32              # steps of layer 0 the oracle is timed on and parity-checked against
-CPU_PASSES_ALL, CPU_PASSES_ONE = 8, 3   # repetitions of those steps for the two timings (about 10 s of CPU work in all)
+CPU_PASSES_ALL, CPU_PASSES_ONE = 20, 8   # repetitions of those steps for the two timings (about 20 s of CPU work in all)
 K_SWEEP = (0.001, 0.005, 0.01, 0.05)   # further fractions of K timed for the latency-vs-k list
 KCHUNK_SWEEP = (0, 8, 16, 32, 64, 128)  # channels per 1024: k = 0, 32, ..., 512 per 4096 input channels
 CFG = 2                     # workload index used for seeding (the second of the five workloads)
@@ -308,10 +308,17 @@ def main() -> int:
 
     gemv_shapes = per_shape(gemv_launches, call_wbytes, HBM_PEAK_GBS)
     fetch_shapes = per_shape(fetch_launches, call_rbytes, LINK_PEAK_GBS)
-    g_us_step = sum(r["avg_launch_us"] for r in gemv_shapes)          # base-GEMV kernel time per step
-    f_us_step = sum(r["avg_launch_us"] for r in fetch_shapes)
+    # The roofline figures take the launch duration from the timed region itself: a base-only step is its
+    # n_calls base-GEMV launches back to back and nothing else, a compensated step its n_calls one-grid
+    # launches, so (HIP events around the replays) / launches is the average launch duration including the
+    # gap to the next launch.  The eager pass above gives the split by launch shape; a kernel launched
+    # eagerly starts on an idle GPU and takes a few per cent longer than inside back-to-back replays.
+    g_us_step = ms_base * 1e3
+    f_us_step = ms_step * 1e3
     gemv_gbs = gemv_bytes / g_us_step / 1e3 if g_us_step > 0 else 0.0
     fetch_gbs = fetch_bytes / f_us_step / 1e3 if f_us_step > 0 else 0.0
+    g_us_eager = sum(r["avg_launch_us"] for r in gemv_shapes)
+    f_us_eager = sum(r["avg_launch_us"] for r in fetch_shapes)
     traffic = traffic_from_profile() if (args.grouping == "grouped" and not args.separate_accumulate) else None
 
     if args.pmc_calibrate:
@@ -388,8 +395,8 @@ def main() -> int:
         "compensation_added_pct": round(added_pct, 1),
         "roofline": {
             "kernel": f"gemv_kernel<PACK_U3> (base GEMV incl. the sum of its K-slices, {n_calls} launches per step; timed on "
-                      "the base-only steps of this run: in a compensated step the same device code runs inside "
-                      "compensated_gemv_kernel, whose duration is set by the host link)",
+                      "the base-only steps of this run, which consist of these launches alone: in a compensated step "
+                      "the same device code runs inside compensated_gemv_kernel, whose duration is set by the host link)",
             "bound": "hbm",
             "achieved": round(gemv_gbs, 1),
             "peak": HBM_PEAK_GBS,
@@ -399,14 +406,17 @@ def main() -> int:
             "traffic_source": TRAFFIC_PROFILE if traffic else None,
             "algorithmic_bytes_per_launch": round(gemv_bytes / n_calls),
             "avg_launch_us": round(g_us_step / n_calls, 3),
+            "avg_launch_us_source": "HIP events around the timed base-only replays / launches (includes the gaps between launches)",
             "per_launch_shape": gemv_shapes,
-            "note": "the kernel includes the sum of its K-slices and writes y; an uncompensated GEMV call is this one launch "
-                    "(a separate accumulate kernel of 3.9 us per call is no longer launched and was never part of this figure)",
+            "per_launch_shape_source": "dispatch timestamps of eager launches of the same steps "
+                                       f"({round(g_us_eager, 2)} us per step: a kernel launched eagerly starts on an idle GPU)",
+            "note": "the kernel includes the sum of its K-slices (one atomic per column and slice) and writes y; an "
+                    "uncompensated GEMV call is this one launch",
         },
         "link_roofline": {
             "kernel": f"compensated_gemv_kernel<PACK_U3, fp16 rows> (selection + zero-copy residual fetch + residual GEMV "
-                      f"in its first workgroups, base GEMV in the others, sum of all partial rows by the last workgroup of "
-                      f"a tile; {n_calls} launches per step)",
+                      f"in its first workgroups, base GEMV in the others, all part sums added with one atomic per column; "
+                      f"{n_calls} launches per step, which are all a compensated step consists of)",
             "bound": "host_link",
             "achieved": round(fetch_gbs, 2),
             "peak": LINK_PEAK_GBS,
@@ -415,11 +425,13 @@ def main() -> int:
             "frac_of_measured_link_ceiling": round(fetch_gbs / LINK_MEASURED_GBS, 4),
             "algorithmic_bytes_per_launch": round(fetch_bytes / n_calls),
             "avg_launch_us": round(f_us_step / n_calls, 3),
+            "avg_launch_us_source": "HIP events around the timed replays / launches (includes the gaps between launches)",
             "per_launch_shape": fetch_shapes,
+            "per_launch_shape_source": f"dispatch timestamps of eager launches of the same steps ({round(f_us_eager, 2)} us per step)",
         },
         "vs_k": vs_k,
         "selection_in_kernel": select_cost,
-        "accumulate": "inside the producing kernels (last workgroup of a 64-column tile)" if acc_us is None
+        "accumulate": "inside the producing kernels (one fixed-point atomic per column and producer)" if acc_us is None
                       else f"separate kernel, {acc_us} us per launch",
         "setup_s": round(setup_s, 1),
         "launch": f"hip-graph replay, {gs} steps per graph" if args.graph else "eager",
@@ -432,7 +444,7 @@ def main() -> int:
                                            "on this GPU, see per_launch_shape and configs.llama3_70b_layer"},
             "compensation_added_pct_at_k_2pct": {"target": 10.0, "achieved": round(added_pct, 1),
                                                  "met": bool(added_pct <= 10.0),
-                                                 "note": "8.65 MB per step over a 57.5 GB/s link take 150 us against 36 us for "
+                                                 "note": f"8.65 MB per step over a 57.5 GB/s link take 150 us against {ms_base * 1e3:.0f} us for "
                                                          "the base GEMVs: link-bound by construction at this k, see "
                                                          "paper_operating_point"},
         },
@@ -679,9 +691,13 @@ def main() -> int:
                 "link_GBs_whole_step": round(rbytes / (ms_c * 1e-3) / 1e9, 2),
                 "base_only_step_HBM_GBs": round(wbytes / (ms_b * 1e-3) / 1e9, 1),
                 "base_gemv_roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                       "achieved": round(wbytes / per_step_layers / kern_us / 1e3, 1),
-                                       "frac": round(wbytes / per_step_layers / kern_us / 1e3 / HBM_PEAK_GBS, 4),
-                                       "per_launch_shape": shapes_rows},
+                                       "achieved": round(wbytes / (ms_b * 1e-3) / 1e9, 1),
+                                       "frac": round(wbytes / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                       "source": "HIP events around the timed base-only replays, which consist of the "
+                                                 "base-GEMV launches alone",
+                                       "per_launch_shape": shapes_rows,
+                                       "per_launch_shape_source": "dispatch timestamps of eager launches "
+                                                                  f"({round(kern_us, 2)} us per layer)"},
                 "setup_s": round(time.time() - t0, 1),
             }
             ws2.close()

@@ -29,7 +29,7 @@ FetchPlan fetch_plan(int rfmt, const MultiShape& sh, int k, int row_split, bool 
     // wavefronts that share the rows of one segment
     int per_segment = row_split > 0 ? row_split : (waves + p.segments - 1) / p.segments;
     // fp16 rows: one workgroup per segment is enough once there are eight segments (64 wavefronts already
-    // fill the link, and the tile has one partial row fewer to add); measured 0.6 % on the Llama-3-8B layer
+    // fill the link, and every column has one part sum fewer to add); measured 0.6 % on the Llama-3-8B layer
     if (row_split <= 0 && !in_hbm && rfmt == 0 && p.segments >= 8 && per_segment > kWavesPerBlock)
         per_segment = kWavesPerBlock;
     if (per_segment > kMaxFetchSlices * kWavesPerBlock) per_segment = kMaxFetchSlices * kWavesPerBlock;

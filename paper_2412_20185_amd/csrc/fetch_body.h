@@ -14,7 +14,7 @@
 // segment are spread over the wavefronts of the workgroup (and over `slices`
 // workgroups when one workgroup does not put enough requests in flight: the
 // knob that plays the role of n_tb in Section 4.4); the wavefronts' sums meet
-// in LDS and the workgroup leaves ONE fp32 partial row per segment.
+// in LDS and the workgroup contributes ONE fp32 part sum per column of the segment.
 //
 // Selection inside the kernel (SELECT_NCH > 0): every workgroup first runs the
 // exact top-k of select_block.h on x for itself and keeps sc_indices and

@@ -10,9 +10,9 @@
 // runs 5-7x slower.  Inside one grid the fetch workgroups are dispatched first
 // (lowest workgroup ids), the GEMV workgroups fill the rest of the chip and
 // finish while the fetch workgroups are still waiting for the host link, and
-// whichever workgroup completes a 64-column tile of the output last adds its
-// partial rows up (finalize.h), so nothing has to be joined and nothing else
-// has to be launched.  (fp16 and 4-bit residuals; the 2- and 8-bit variants
+// every workgroup adds its part sums into the per-column accumulators, the
+// last arrival writing y (finalize.h), so nothing has to be joined and nothing
+// else has to be launched.  (fp16 and 4-bit residuals; the 2- and 8-bit variants
 // of the bit-width study use the separate kernels.)  How many workgroups fetch (the paper's n_tb,
 // Section 4.4) follows from the number of wavefronts that share the rows of a
 // column segment (decdec_ws_set_fetch_split).

@@ -13,8 +13,8 @@ namespace decdec {
 constexpr int kBlockThreads = 512;
 constexpr int kWavesPerBlock = kBlockThreads / 64;
 
-constexpr int kMaxGemvSlices = 16;   // fp32 partial rows the base GEMV may write
-constexpr int kMaxFetchSlices = 16;  // fp32 partial rows the residual kernel may write
+constexpr int kMaxGemvSlices = 16;   // part sums per column the base GEMV may contribute (K-slices)
+constexpr int kMaxFetchSlices = 16;  // part sums per column the residual kernel may contribute (row slices)
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectMaxK = 65536;
 
@@ -60,14 +60,14 @@ struct FetchOperands {
 };
 
 // gemv.hip ---------------------------------------------------------------
-// part: fp32 [slices][Ntot]; *slices_out receives the number of rows written.
+// part: fp32 [slices][Ntot], written only when fa.acc is null (a separate kernel adds the rows); may be null otherwise.
 struct FinalizeArgs;
 // wpb: wavefronts per workgroup (4, 8 or 16).
 hipError_t launch_gemv(int kind, const MultiShape& sh, const GemvOperands& op, const void* x, float* part,
                        int slices, int gpw, int wpb, const FinalizeArgs& fa, hipStream_t stream,
                        const KernelTimer* tm = nullptr);
 // How K is cut: workgroups of `wpb` wavefronts, each wavefront walking `gpw` groups of 128 input channels,
-// `slices` workgroups (and fp32 partial rows) per 64-column tile.  Requests of 0 leave the choice to the
+// `slices` workgroups (and part sums per column) per 64-column tile.  Requests of 0 leave the choice to the
 // library; inside the one-grid kernel wpb is kWavesPerBlock.
 struct GemvPlan {
     int wpb, gpw, slices;
@@ -86,7 +86,7 @@ hipError_t launch_select_bucket(const void* x, int K, int k_chunk, float b0, flo
 // fetch.hip --------------------------------------------------------------
 // How the residual kernel is laid out: `segments` column segments (one 16-byte piece per lane and row; all
 // matrices of the call together) x `slices` workgroups per segment; `row_waves` wavefronts of each workgroup
-// share its rows.  cpart is fp32 [slices][Ntot].
+// share its rows.  cpart is fp32 [slices][Ntot] (used only when fa.acc is null).
 struct FetchPlan {
     int segments, slices, row_waves;
 };
@@ -108,7 +108,7 @@ hipError_t launch_compensated_gemv(int kind, int rfmt, const MultiShape& sh, con
                                    const FinalizeArgs& fa, hipStream_t stream, const KernelTimer* tm = nullptr);
 
 // accumulate.hip ---------------------------------------------------------
-// y_m[n] = fp16( sum_s gpart[s][col0[m]+n] + sum_r cpart[r][col0[m]+n] )
+// y_m[n] = fp16( sum_s gpart[s][col0[m]+n] + sum_r cpart[r][col0[m]+n] ), the terms added in the fixed point of finalize.h
 hipError_t launch_accumulate(const MultiShape& sh, void* const* y, const float* gpart, int gslices,
                              const float* cpart, int cslices, hipStream_t stream, const KernelTimer* tm = nullptr);
 

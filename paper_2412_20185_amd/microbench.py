@@ -2,7 +2,7 @@
 
     python -m paper_2412_20185_amd.microbench gemv     base GEMV kernel per shape: us, GB/s, fraction of 8 TB/s
     python -m paper_2412_20185_amd.microbench gemvshape  base GEMV launch shapes (waves per workgroup x groups per wave)
-                                                       and the three ways of adding its partial rows
+                                                       and the three ways of adding its K-slices
     python -m paper_2412_20185_amd.microbench selcost  cost of the exact selection: its own kernel, and inside the one-grid kernel
     python -m paper_2412_20185_amd.microbench fetch    residual fetch kernel per shape and number of wavefronts per column segment: us, GB/s
     python -m paper_2412_20185_amd.microbench ksweep   latency of a Llama-3-8B layer versus k (4-bit weights),
@@ -85,8 +85,8 @@ def gemv(args):
 
 def gemvshape(args):
     """Launch shapes of the base GEMV (k = 0): wavefronts per workgroup x groups of 128 input channels per
-    wavefront, with the partial rows added by the accumulate kernel (acc), by the last workgroup of a tile
-    (ink) or not needed at all because one workgroup covers all of K (direct).  Kernel durations from the
+    wavefront, with the K-slices added by the accumulate kernel (acc), inside the kernel with one atomic per
+    column and slice (ink) or not at all because one workgroup covers all of K (direct).  Kernel durations from the
     dispatch timestamps; call = wall time per call over HIP-graph replays of 16 back-to-back calls on
     rotating weight copies."""
     import time

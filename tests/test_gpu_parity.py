@@ -220,8 +220,8 @@ def test_caller_supplied_selection_matches_internal_selection(ws):
 
 
 def test_repeated_calls_are_bitwise_reproducible(ws):
-    """The accumulate adds partial rows in a fixed order: no run-to-run variation,
-    and nothing left over in the workspace from a previous, larger call."""
+    """The part sums are added as integers (fixed point), so the order of arrival cannot show: no
+    run-to-run variation, and nothing left over in the workspace from a previous, larger call."""
     K, N = 4096, 1024
     p = Problem(workloads.weights(61, 0, 0, K, N), 3)
     big = Problem(workloads.weights(62, 0, 0, 1024, 4096), 4)
@@ -283,10 +283,9 @@ def test_multi_rejects_mismatched_matrices(ws):
 
 
 def test_in_kernel_accumulate_equals_separate_kernel_bitwise(ws):
-    """The last producer of a tile adds the partial rows in the same fixed order
-    as the stand-alone accumulate kernel: both modes must agree bit for bit, on
-    every repetition (a visibility bug between the chip's L2 caches would show
-    up as an occasional stale partial row)."""
+    """The producers' atomics into the column accumulators and the stand-alone accumulate kernel over
+    fp32 partial rows add the same fixed-point terms: both modes must agree bit for bit, on every
+    repetition (a lost or doubled arrival would show up as an occasional wrong or missing column)."""
     K, N = 4096, 4096
     p = Problem(workloads.weights(63, 0, 0, K, N), 3)
     d = p.device()
@@ -334,8 +333,8 @@ def test_selection_inside_fetch_kernel_equals_selection_kernel(ws, K, N, k):
 @pytest.mark.parametrize("wfmt,bits,rfmt", [("uniform", 3, "fp16"), ("uniform", 4, "int4"), ("lut", 3, "fp16")])
 def test_all_layouts_of_the_work_give_the_same_bits(ws, wfmt, bits, rfmt):
     """Separate kernels on one stream and the paper's two-stream arrangement compute
-    the same partial rows and add them in the same order: identical bits.  The fused
-    kernel splits K over larger workgroups, so its fp32 partial sums may round
+    the same part sums and add them as integers: identical bits.  The fused
+    kernel may split K over workgroups of another size, so its fp32 part sums may round
     differently; it is held to the oracle tolerance like the others."""
     K, N = 4096, 1536
     p = Problem(workloads.weights(65, 0, 0, K, N), bits, wfmt=wfmt, rfmt=rfmt, lut_iters=2,

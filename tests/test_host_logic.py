@@ -31,7 +31,7 @@ def test_strerror_and_buffer_size():
     # Section 4.3: 1433 channels need 1433 * (4 + 2) bytes
     assert dd.decdec_sc_buffer_bytes(1433) == 8598
     assert dd.decdec_sc_buffer_bytes(0) == 0
-    # the partial rows of the deterministic accumulate: (16 + 16) rows of maxN floats
+    # the partial rows of the optional separate accumulate kernel: (16 + 16) rows of maxN floats
     assert dd.decdec_partial_buffer_bytes(28672) == 32 * 28672 * 4
     assert dd.decdec_partial_buffer_bytes(0) == 0
     assert "static" in dd.decdec_strerror(-6)
