@@ -53,15 +53,19 @@ def log(msg: str):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def traffic_from_profile():
+def traffic_from_profile(launch_shapes: str):
     """HBM bytes per base-GEMV launch of the default workload as the committed counter profile states them
-    (a line `hbm_traffic_bytes_per_launch: N`), or None when the file has no such line."""
+    (a line `hbm_traffic_bytes_per_launch: N`), or None when the file has no such line or was taken with
+    other launch shapes than the library uses now (its line `launch_shapes: ...` against `launch_shapes`)."""
     try:
         text = open(os.path.join(ROOT, TRAFFIC_PROFILE)).read()
     except OSError:
         return None
     m = re.search(r"hbm_traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
-    return float(m.group(1)) if m else None
+    s = re.search(r"launch_shapes:\s*(.+)", text)
+    if not m or not s or s.group(1).strip() != launch_shapes:
+        return None
+    return float(m.group(1))
 
 
 class StepRunner:
@@ -319,7 +323,11 @@ def main() -> int:
     fetch_gbs = fetch_bytes / f_us_step / 1e3 if f_us_step > 0 else 0.0
     g_us_eager = sum(r["avg_launch_us"] for r in gemv_shapes)
     f_us_eager = sum(r["avg_launch_us"] for r in fetch_shapes)
-    traffic = traffic_from_profile() if (args.grouping == "grouped" and not args.separate_accumulate) else None
+    # workgroups x threads of the step's base-GEMV launches under the library's current plan: the counter
+    # profile is only quoted while it was taken with the same ones
+    launch_shapes = " ".join("%s %dx%d" % ((call_names[c],) + ws.gemv_launch_shape(
+        Kof[order[c][1][0]], sum(lin0[n].N for n in order[c][1]))[:2]) for c in range(n_calls))
+    traffic = traffic_from_profile(launch_shapes) if (args.grouping == "grouped" and not args.separate_accumulate) else None
 
     if args.pmc_calibrate:
         # A plain elementwise kernel of known size: reads 256 MiB, writes 256 MiB.  The ratio of its
@@ -404,6 +412,7 @@ def main() -> int:
             "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
             "traffic": round(traffic) if traffic else None,
             "traffic_source": TRAFFIC_PROFILE if traffic else None,
+            "launch_shapes": launch_shapes,
             "algorithmic_bytes_per_launch": round(gemv_bytes / n_calls),
             "avg_launch_us": round(g_us_step / n_calls, 3),
             "avg_launch_us_source": "HIP events around the timed base-only replays / launches (includes the gaps between launches)",

@@ -189,6 +189,15 @@ int decdec_ws_set_gemv_split(decdec_ws* ws, int32_t groups_per_wave);
  * residual term (k == 0) the kernel writes y itself and nothing else is
  * launched. */
 int decdec_ws_set_gemv_waves(decdec_ws* ws, int32_t waves_per_workgroup);
+/* Host-side query, nothing is enqueued: the grid the base GEMV kernel of an
+ * uncompensated call (k == 0) over K input channels and N_total output columns
+ * (all matrices of a decdec_gemv_multi call together) would be launched with
+ * under this workspace's current settings: number of workgroups, threads per
+ * workgroup, K-slices per 64-column tile.  Any output pointer may be NULL.
+ * Benchmarks use it to tell whether a stored profile still describes the
+ * kernels that run. */
+int decdec_ws_gemv_launch_shape(const decdec_ws* ws, int32_t K, int32_t N_total, int32_t* workgroups,
+                                int32_t* threads, int32_t* k_slices);
 
 /* Kernel timing for benchmarks.  capacity > 0 allocates that many sets of HIP
  * events (set-up call: allocates, synchronises) and makes every later

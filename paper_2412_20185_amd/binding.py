@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = (
     "decdec_ws_read_selection", "decdec_ws_set_fetch_split", "decdec_ws_set_profiling", "decdec_ws_set_gemv_split", "decdec_ws_set_gemv_waves", "decdec_ws_set_inkernel_accumulate", "decdec_ws_set_separate_select", "decdec_ws_set_mode",
     "decdec_ws_read_profile", "decdec_packed_bytes", "decdec_pack_weights", "decdec_unpack_weights",
     "decdec_pack_residual_int4", "decdec_pack_residual_int", "decdec_select_topk", "decdec_select_bucket", "decdec_gemv", "decdec_gemv_idx", "decdec_gemv_multi",
-    "decdec_partial_buffer_bytes", "decdec_ws_read_profile_launches", "decdec_ws_forget_pointer",
+    "decdec_partial_buffer_bytes", "decdec_ws_read_profile_launches", "decdec_ws_forget_pointer", "decdec_ws_gemv_launch_shape",
     "decdec_ws_pointer_queries", "decdec_gemv_static",
     "decdec_quantize_uniform", "decdec_residual_f32", "decdec_quantize_residual", "decdec_strerror", "decdec_last_hip_error", "decdec_check_pinned", "decdec_check_residual_pointer",
 )
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
     L.decdec_ws_set_gemv_split.argtypes = [vp, i32]
     L.decdec_ws_set_gemv_waves.argtypes = [vp, i32]
     L.decdec_ws_set_inkernel_accumulate.argtypes = [vp, i32]
+    L.decdec_ws_gemv_launch_shape.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
     L.decdec_ws_set_separate_select.argtypes = [vp, i32]
     L.decdec_ws_set_mode.argtypes = [vp, i32]
     L.decdec_ws_read_profile.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -184,6 +185,13 @@ class Workspace:
 
     def set_gemv_waves(self, waves_per_workgroup: int):
         _check(lib().decdec_ws_set_gemv_waves(self.handle, waves_per_workgroup), "decdec_ws_set_gemv_waves")
+
+    def gemv_launch_shape(self, K: int, N_total: int):
+        """(workgroups, threads per workgroup, K-slices) of the base GEMV kernel of a k = 0 call."""
+        wg, th, sl = C.c_int32(), C.c_int32(), C.c_int32()
+        _check(lib().decdec_ws_gemv_launch_shape(self.handle, K, N_total, C.byref(wg), C.byref(th), C.byref(sl)),
+               "decdec_ws_gemv_launch_shape")
+        return wg.value, th.value, sl.value
 
     def set_profiling(self, capacity: int):
         _check(lib().decdec_ws_set_profiling(self.handle, capacity), "decdec_ws_set_profiling")

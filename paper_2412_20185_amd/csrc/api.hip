@@ -381,6 +381,17 @@ int decdec_ws_set_gemv_waves(decdec_ws* ws, int32_t waves_per_workgroup) {
     return DECDEC_OK;
 }
 
+int decdec_ws_gemv_launch_shape(const decdec_ws* ws, int32_t K, int32_t N_total, int32_t* workgroups,
+                                int32_t* threads, int32_t* k_slices) {
+    if (ws == nullptr || K <= 0 || K % kGroup != 0 || N_total <= 0 || N_total % kTileCols != 0) return DECDEC_EINVAL;
+    const long tiles = N_total / kTileCols;
+    const GemvPlan gp = gemv_plan(tiles, K / kGroup, ws->core.gemv_gpw, ws->core.gemv_wpb);
+    if (workgroups) *workgroups = (int32_t)(tiles * gp.slices);
+    if (threads) *threads = gp.wpb * 64;
+    if (k_slices) *k_slices = gp.slices;
+    return DECDEC_OK;
+}
+
 int decdec_ws_read_selection(const decdec_ws* ws, int32_t k, int32_t* idx_host, void* xsel_f16_host) {
     if (ws == nullptr || k < 0 || k > ws->core.maxk) return DECDEC_EINVAL;
     // The selection may have been written by a kernel on any stream of the caller's: wait for the device.

@@ -177,3 +177,26 @@ def test_per_launch_profile_lists_every_launch_in_order(prob):
         ws.set_profiling(0)
     finally:
         ws.close()
+
+
+def test_launch_shape_query_follows_the_workspace_settings():
+    """The host-side query returns the grid of the base GEMV of a k = 0 call: workgroups = 64-column tiles
+    x K-slices, and waves x groups per wave x slices covers the K / 128 groups."""
+    ws = dd.Workspace(14336, 28672, 0)
+    try:
+        for Kq, Nq in ((4096, 4096), (4096, 6144), (4096, 28672), (14336, 4096), (8192, 1024)):
+            wg, threads, slices = ws.gemv_launch_shape(Kq, Nq)
+            assert threads in (256, 512, 1024) and wg == (Nq // 64) * slices and 1 <= slices <= 16
+        ws.set_gemv_waves(8)
+        ws.set_gemv_split(2)
+        assert ws.gemv_launch_shape(4096, 4096) == (64 * 2, 512, 2)          # 32 groups / (8 waves x 2)
+        ws.set_gemv_split(1)
+        assert ws.gemv_launch_shape(14336, 4096) == (64 * 14, 512, 14)       # 112 groups / 8 waves
+        ws.set_gemv_waves(4)
+        assert ws.gemv_launch_shape(14336, 4096) == (64 * 14, 256, 14)       # 28 slices asked: capped at 16 by two groups per wave
+        ws.set_gemv_waves(0)
+        ws.set_gemv_split(0)
+        with pytest.raises(dd.DecdecError):
+            ws.gemv_launch_shape(4000, 4096)
+    finally:
+        ws.close()

@@ -78,6 +78,7 @@ def test_validation_without_gpu():
         dd.decdec_pack_weights(good, codes)                                           # code >= 2^3
     with pytest.raises(dd.DecdecError):
         dd.decdec_pack_residual_int4(np.full((4, 64), -8, np.int8))
+    assert L.decdec_ws_gemv_launch_shape(None, 4096, 4096, None, None, None) == -1
     h = C.c_void_p()
     assert L.decdec_ws_create(0, 64, 0, C.byref(h)) == -1
     assert L.decdec_ws_create(128, 64, 129, C.byref(h)) == -1
