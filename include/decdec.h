@@ -294,8 +294,10 @@ int decdec_select_bucket(const void* x_f16_dev, int32_t K, int32_t k_chunk, floa
  *   k              salient channels, 0 <= k <= min(K, maxk of ws)
  *   y_f16_dev      dev fp16 [N] out
  * By default the base GEMV and steps 1-3 run side by side inside one kernel on
- * `stream` (see decdec_ws_set_mode); the sum is formed on `stream` after both
- * (fp32 accumulation throughout, one rounding to fp16).  k == 0 equals the
+ * `stream` (see decdec_ws_set_mode) and add their part sums themselves
+ * (fp32 accumulation inside a workgroup, the workgroups' sums added in fixed
+ * point, one rounding to fp16: decdec_ws_set_inkernel_accumulate); the result
+ * does not depend on the order in which workgroups finish.  k == 0 equals the
  * plain quantised GEMV.
  * The call only enqueues kernels (plus, in TWO_STREAMS mode, event records and
  * waits on the workspace's second stream), so it may be captured into a HIP
