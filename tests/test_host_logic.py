@@ -176,3 +176,25 @@ def test_int2_int8_residual_rows():
                       (np.zeros((1, 8), np.int8), 8), (np.zeros((1, 64), np.int8), 3)):
         with pytest.raises(dd.DecdecError):
             dd.decdec_pack_residual_int(bad, bits)
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with warnings as errors, and a C program that
+    calls host-only entry points links against the shared library and runs (no GPU needed)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_decdec.c"
+    src.write_text('#include <stdio.h>\n#include "decdec.h"\n'
+                   "int main(void) {\n"
+                   "    decdec_desc d = {256, 128, 3, DECDEC_W_UNIFORM_G128, DECDEC_R_FP16};\n"
+                   '    printf("%lu %lu %s\\n", (unsigned long)decdec_packed_bytes(&d),\n'
+                   "           (unsigned long)decdec_sc_buffer_bytes(1433), decdec_strerror(DECDEC_EINVAL));\n"
+                   "    return decdec_ws_destroy(NULL);\n}\n")
+    libdir = os.path.join(ROOT, "paper_2412_20185_amd")
+    exe = tmp_path / "use_decdec"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-ldecdec", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 2)
+    assert out[0] == str(256 * 128 * 3 // 8) and out[1] == "8598" and "invalid" in out[2]
