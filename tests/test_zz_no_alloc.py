@@ -61,3 +61,25 @@ def test_static_entry_point_rejects_sizes_beyond_its_scratch():
     ok_shape = dd.Desc(8192, 4096, 3)
     assert L.decdec_gemv_static(C.byref(ok_shape), P, P, P, P, P, None, dd.STATIC_MAX_SELECTED + 1, P, None) == -6
     assert "static" in dd.decdec_strerror(-6)
+
+
+def test_static_entry_point_at_the_width_of_gate_plus_up():
+    """N = 28672 (inside DECDEC_STATIC_MAX_N = 32768), stored parameters drawn at random in the library's
+    formats: the static entry point against the workspace entry point, bit for bit, then a narrow call."""
+    from paper_2412_20185_amd.layer import StoredLinear
+    wide = StoredLinear.random(4096, 28672, 3, dd.W_UNIFORM_G128, 16, seed=5)
+    narrow = StoredLinear.random(4096, 1024, 3, dd.W_UNIFORM_G128, 16, seed=6)
+    ws = dd.Workspace(4096, 28672, 128)
+    try:
+        for step, (lin, k) in enumerate([(wide, 81), (narrow, 81), (wide, 4)]):
+            N = lin.desc.N
+            x = torch.from_numpy(workloads.x_gauss_outliers(98, 0, 0, step, 4096)).cuda()
+            y_ws = torch.full((N,), float("nan"), dtype=torch.float16, device="cuda")
+            y_st = torch.full((N,), float("nan"), dtype=torch.float16, device="cuda")
+            lin.gemv(x, k, y_ws, ws)
+            dd.decdec_gemv_static(lin.desc, x, lin.Wq, lin.scales, lin.zeros, lin.R, lin.R_scales, k, y_st)
+            torch.cuda.synchronize()
+            a, b = y_ws.cpu().numpy(), y_st.cpu().numpy()
+            assert np.all(np.isfinite(a.astype(np.float32))) and np.array_equal(a.view(np.uint16), b.view(np.uint16)), step
+    finally:
+        ws.close()
