@@ -99,16 +99,24 @@ class StepRunner:
                 i += 1
 
     def timed(self, n: int, mode, warmup: int = 0) -> float:
-        """Milliseconds per step over exactly n steps (n a multiple of gs when graphs are on)."""
+        """Milliseconds per step over exactly n steps (n a multiple of gs when graphs are on), by the host's
+        clock around the synchronised region.  self.event_ms receives the same region as two HIP events on
+        the launching stream saw it (no host launch or synchronisation latency inside): what the roofline
+        figures use."""
         if self.use_graph:
             self.run(0, n, mode)                 # capture outside the timed region
         if warmup:
             self.run(0, warmup, mode)
+        ev0, ev1 = (self.torch.cuda.Event(enable_timing=True) for _ in range(2))
         self.torch.cuda.synchronize()
         t0 = time.perf_counter()
+        ev0.record()                             # on the current stream, the one replays and eager calls go to
         self.run(0, n, mode)
+        ev1.record()
         self.torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / n
+        host_ms = (time.perf_counter() - t0) * 1e3 / n
+        self.event_ms = ev0.elapsed_time(ev1) / n
+        return host_ms
 
     def spread(self, samples: int, mode, span: int):
         """Graph replays (gs steps each) enqueued back to back with an event between every two: sorted
@@ -253,8 +261,10 @@ def main() -> int:
     # ------------------------------------------------------------ timed region
     runner.run(0, args.warmup, True)
     ms_step = runner.timed(args.steps, True)
+    ev_ms_step = runner.event_ms
     runner.run(0, args.warmup, False)
     ms_base = runner.timed(args.steps, False)
+    ev_ms_base = runner.event_ms
     log(f"headline: {ms_step * 1e3:.1f} us per step, base-only {ms_base * 1e3:.1f} us")
 
     # latency against k (the metric is quoted "vs k"): the same steps at other fractions of K
@@ -317,8 +327,8 @@ def main() -> int:
     # launches, so (HIP events around the replays) / launches is the average launch duration including the
     # gap to the next launch.  The eager pass above gives the split by launch shape; a kernel launched
     # eagerly starts on an idle GPU and takes a few per cent longer than inside back-to-back replays.
-    g_us_step = ms_base * 1e3
-    f_us_step = ms_step * 1e3
+    g_us_step = ev_ms_base * 1e3
+    f_us_step = ev_ms_step * 1e3
     gemv_gbs = gemv_bytes / g_us_step / 1e3 if g_us_step > 0 else 0.0
     fetch_gbs = fetch_bytes / f_us_step / 1e3 if f_us_step > 0 else 0.0
     g_us_eager = sum(r["avg_launch_us"] for r in gemv_shapes)
@@ -415,7 +425,8 @@ def main() -> int:
             "launch_shapes": launch_shapes,
             "algorithmic_bytes_per_launch": round(gemv_bytes / n_calls),
             "avg_launch_us": round(g_us_step / n_calls, 3),
-            "avg_launch_us_source": "HIP events around the timed base-only replays / launches (includes the gaps between launches)",
+            "avg_launch_us_source": "two HIP events on the launching stream around the timed base-only steps / launches in them "
+                                    "(includes the gaps between launches, not the host's launch and synchronisation latency)",
             "per_launch_shape": gemv_shapes,
             "per_launch_shape_source": "dispatch timestamps of eager launches of the same steps "
                                        f"({round(g_us_eager, 2)} us per step: a kernel launched eagerly starts on an idle GPU)",
@@ -434,7 +445,7 @@ def main() -> int:
             "frac_of_measured_link_ceiling": round(fetch_gbs / LINK_MEASURED_GBS, 4),
             "algorithmic_bytes_per_launch": round(fetch_bytes / n_calls),
             "avg_launch_us": round(f_us_step / n_calls, 3),
-            "avg_launch_us_source": "HIP events around the timed replays / launches (includes the gaps between launches)",
+            "avg_launch_us_source": "two HIP events on the launching stream around the timed steps / launches in them",
             "per_launch_shape": fetch_shapes,
             "per_launch_shape_source": f"dispatch timestamps of eager launches of the same steps ({round(f_us_eager, 2)} us per step)",
         },
@@ -659,6 +670,7 @@ def main() -> int:
             r = StepRunner(torch, step2, gs2, math.lcm(nlayers if one_layer else 1, npool), bool(args.graph))
             ms_c = r.timed(steps2 - steps2 % gs2 or gs2, True, warmup=gs2)
             ms_b = r.timed(steps2 - steps2 % gs2 or gs2, False, warmup=gs2)
+            ev_ms_b = r.event_ms
             per_step_layers = 1 if one_layer else nlayers
             ngemv = per_step_layers * len(shp)
             rbytes = per_step_layers * sum(kof(K) * N * rbits // 8 for _, K, N, _ in shp)
@@ -700,10 +712,10 @@ def main() -> int:
                 "link_GBs_whole_step": round(rbytes / (ms_c * 1e-3) / 1e9, 2),
                 "base_only_step_HBM_GBs": round(wbytes / (ms_b * 1e-3) / 1e9, 1),
                 "base_gemv_roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                       "achieved": round(wbytes / (ms_b * 1e-3) / 1e9, 1),
-                                       "frac": round(wbytes / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                                       "source": "HIP events around the timed base-only replays, which consist of the "
-                                                 "base-GEMV launches alone",
+                                       "achieved": round(wbytes / (ev_ms_b * 1e-3) / 1e9, 1),
+                                       "frac": round(wbytes / (ev_ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                       "source": "two HIP events on the launching stream around the timed base-only steps, "
+                                                 "which consist of the base-GEMV launches alone",
                                        "per_launch_shape": shapes_rows,
                                        "per_launch_shape_source": "dispatch timestamps of eager launches "
                                                                   f"({round(kern_us, 2)} us per layer)"},
